@@ -1,0 +1,164 @@
+"""CPU oracle for reduced-ring secret-shared DReLU / ReLU (test infrastructure).
+
+Thin ctypes/numpy access to oracle/hb_ref.c.  Only tests, the smoke check and the
+benchmark's cpu_baseline leg import this package; the product library does not.
+"""
+import ctypes
+import os
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+_lib = None
+
+WHAT_DRELU, WHAT_RELU, WHAT_SUM, WHAT_SIGN, WHAT_SLICE = 0, 1, 2, 3, 4
+
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+_u64 = ctypes.c_uint64
+_int = ctypes.c_int
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        from .build import build as _build_oracle
+        path = _build_oracle(force=False)
+        L = ctypes.CDLL(path)
+        L.hb_ref_mix64.restype = _u64
+        L.hb_ref_mix64.argtypes = [_u64]
+        L.hb_ref_sm_next.restype = _u64
+        L.hb_ref_sm_next.argtypes = [_u64p]
+        L.hb_ref_sm.restype = _u64
+        L.hb_ref_sm.argtypes = [_u64, _u64]
+        L.hb_ref_tensor_seed.restype = _u64
+        L.hb_ref_tensor_seed.argtypes = [_u64, _u64]
+        L.hb_ref_opened_bits.restype = _u64
+        L.hb_ref_opened_bits.argtypes = [_int, _int, _int, _u64]
+        L.hb_ref_and_gate.restype = None
+        L.hb_ref_and_gate.argtypes = [_u64] * 10 + [_u64p, _u64p]
+        L.hb_ref_eval_range.restype = _int
+        L.hb_ref_eval_range.argtypes = [_i64p, _i64p, _u64, _u64, _int, _int, _u64, _int, _int, _i64p, _i64p]
+        L.hb_ref_eval_at.restype = _int
+        L.hb_ref_eval_at.argtypes = [_i64p, _i64p, _u64p, _u64, _int, _int, _u64, _int, _int, _i64p, _i64p]
+        L.hb_ref_drelu.restype = _int
+        L.hb_ref_drelu.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _int, _i64p, _i64p, _u64p]
+        L.hb_ref_relu.restype = _int
+        L.hb_ref_relu.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _int, _i64p, _i64p, _u64p]
+        L.hb_ref_open.restype = _int
+        L.hb_ref_open.argtypes = [_i64p, _i64p, _u64, _int, _int, _i64p]
+        _lib = L
+    return _lib
+
+
+def _as_i64(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint64:
+        a = a.view(np.int64)
+    if a.dtype != np.int64:
+        raise TypeError("shares must be int64 or uint64 arrays, got %s" % a.dtype)
+    return a.reshape(-1)
+
+
+def _ptr(a, typ=_i64p):
+    return a.ctypes.data_as(typ)
+
+
+def mix64(z):
+    return int(lib().hb_ref_mix64(_u64(z & (2**64 - 1))))
+
+
+def sm(seed, j):
+    return int(lib().hb_ref_sm(_u64(seed & (2**64 - 1)), _u64(j)))
+
+
+def sm_sequence(seed, count):
+    """First `count` outputs obtained by stepping the generator one output at a time."""
+    state = _u64(seed & (2**64 - 1))
+    return [int(lib().hb_ref_sm_next(ctypes.byref(state))) for _ in range(count)]
+
+
+def tensor_seed(root_seed, tensor_id):
+    return int(lib().hb_ref_tensor_seed(_u64(root_seed & (2**64 - 1)), _u64(tensor_id)))
+
+
+def opened_bits(relu, k, m, n):
+    return int(lib().hb_ref_opened_bits(int(bool(relu)), k, m, _u64(n)))
+
+
+def and_gate(U0, U1, V0, V1, a0, a1, b0, b1, c0, mask):
+    z0, z1 = _u64(), _u64()
+    lib().hb_ref_and_gate(*[_u64(v) for v in (U0, U1, V0, V1, a0, a1, b0, b1, c0, mask)],
+                          ctypes.byref(z0), ctypes.byref(z1))
+    return int(z0.value), int(z1.value)
+
+
+def evaluate(share0, share1, k, m, seed, what, ring_bits=64, first=0, threads=1):
+    """Run the protocol on a whole array; returns the two share arrays selected by `what`.
+
+    threads > 1 splits the element range into contiguous chunks evaluated by a thread pool
+    (the C routine takes the global index of its first element, so results do not change).
+    """
+    s0, s1 = _as_i64(share0), _as_i64(share1)
+    n = s0.size
+    if s1.size != n:
+        raise ValueError("share arrays differ in length")
+    o0 = np.empty(n, dtype=np.int64)
+    o1 = np.empty(n, dtype=np.int64)
+    L = lib()
+
+    def run(lo, hi):
+        st = L.hb_ref_eval_range(_ptr(s0[lo:hi]), _ptr(s1[lo:hi]), _u64(first + lo), _u64(hi - lo), k, m,
+                                 _u64(seed & (2**64 - 1)), ring_bits, what, _ptr(o0[lo:hi]), _ptr(o1[lo:hi]))
+        if st != 0:
+            raise ValueError("oracle rejected arguments (status %d)" % st)
+
+    threads = max(1, int(threads))
+    if threads == 1 or n < 4096:
+        # n == 0 still validates the arguments
+        if n == 0:
+            st = L.hb_ref_eval_range(None, None, _u64(first), _u64(0), k, m, _u64(seed & (2**64 - 1)),
+                                     ring_bits, what, None, None)
+            if st != 0:
+                raise ValueError("oracle rejected arguments (status %d)" % st)
+        else:
+            run(0, n)
+    else:
+        bounds = np.linspace(0, n, threads + 1).astype(np.int64)
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            list(pool.map(lambda ab: run(int(ab[0]), int(ab[1])), zip(bounds[:-1], bounds[1:])))
+    return o0, o1
+
+
+def evaluate_at(share0, share1, index, k, m, seed, what, ring_bits=64):
+    """Scattered elements: element index[i] of the tensor has share values share0[i], share1[i]."""
+    s0, s1 = _as_i64(share0), _as_i64(share1)
+    idx = np.ascontiguousarray(index, dtype=np.uint64).reshape(-1)
+    if not (s0.size == s1.size == idx.size):
+        raise ValueError("length mismatch")
+    o0 = np.empty(idx.size, dtype=np.int64)
+    o1 = np.empty(idx.size, dtype=np.int64)
+    st = lib().hb_ref_eval_at(_ptr(s0), _ptr(s1), _ptr(idx, _u64p), _u64(idx.size), k, m,
+                              _u64(seed & (2**64 - 1)), ring_bits, what, _ptr(o0), _ptr(o1))
+    if st != 0:
+        raise ValueError("oracle rejected arguments (status %d)" % st)
+    return o0, o1
+
+
+def drelu(share0, share1, k, m, seed, ring_bits=64, threads=1):
+    o0, o1 = evaluate(share0, share1, k, m, seed, WHAT_DRELU, ring_bits, threads=threads)
+    return o0, o1, opened_bits(False, k, m, o0.size)
+
+
+def relu(share0, share1, k, m, seed, ring_bits=64, threads=1):
+    o0, o1 = evaluate(share0, share1, k, m, seed, WHAT_RELU, ring_bits, threads=threads)
+    return o0, o1, opened_bits(True, k, m, o0.size)
+
+
+def open_shares(share0, share1, binary=False, ring_bits=64):
+    s0, s1 = _as_i64(share0), _as_i64(share1)
+    out = np.empty(s0.size, dtype=np.int64)
+    st = lib().hb_ref_open(_ptr(s0), _ptr(s1), _u64(s0.size), int(bool(binary)), ring_bits, _ptr(out))
+    if st != 0:
+        raise ValueError("oracle rejected arguments (status %d)" % st)
+    return out

@@ -1,0 +1,325 @@
+/*
+ * hb_ref.c -- CPU oracle for reduced-ring secret-shared DReLU / ReLU.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, per-element statement
+ * of what the GPU library must compute.  Only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg may use it; the product never calls it and shares
+ * no code, header, table or constant generator with it.
+ *
+ * What it follows (paper = "Approximating ReLU on a Reduced Ring for Efficient
+ * MPC-based Private Inference"):
+ *   - notation x[hi:lo] and shares on Z_2^N ............ Sec. 2.2 "Notations"
+ *   - ReLU = x * DReLU(x) ............................... Eq. 1, Eq. 2
+ *   - A2B by an adder circuit on XOR shares, AND gates
+ *     through Beaver triples, sign = MSB, B2A, 1 - sign . Sec. 2.2 "Evaluating ReLU with GMW"
+ *   - DReLU evaluated on the slice of each share only ... Eq. 3, Sec. 3.1 (example, Thm 1, Thm 2)
+ *   - depth ceil(log2 w) circuit, w-bit fields packed
+ *     into 64-bit words ................................. Sec. 4.2
+ *
+ * The paper leaves the adder, the B2A construction, the triple source and the
+ * party that adds public terms open.  The readings used here (Kogge-Stone with
+ * zeros shifted in, one dealer bit for B2A, party 0 adds every public term,
+ * SplitMix64 dealer streams with L = min(floor(64/w),32) fields per binary
+ * word) are this project's protocol definition; the argument convention is
+ * (k, m) = (lowest kept bit, one past the highest kept bit), w = m - k, i.e.
+ * the paper's x[m:k].
+ *
+ * Pins: every reconstructed quantity (adder sum, sign, DReLU, ReLU, opened-bit
+ * counts, the generator) is pinned by the non-GPU tests against closed forms,
+ * brute force on an 8-bit ring, the paper's worked example and published
+ * generator vectors.  The VALUES OF THE INDIVIDUAL OUTPUT SHARES depend on the
+ * dealer layout chosen by this project and are "parity unpinned" by the paper.
+ *
+ * Everything is integer; ring_bits (N) selects the arithmetic ring Z_2^N,
+ * 1 <= N <= 64.  N = 64 is the production ring, N = 8 is used for brute force.
+ */
+#include <stddef.h>
+#include <stdint.h>
+
+#define HB_REF_OK 0
+#define HB_REF_EINVAL (-1)
+
+/* ------------------------------------------------------------------ */
+/* Dealer randomness: SplitMix64 (public-domain generator).            */
+/* ------------------------------------------------------------------ */
+
+static const uint64_t GAMMA = 0x9E3779B97F4A7C15ULL;
+
+uint64_t hb_ref_mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* One step of a SplitMix64 generator: advance the state, return the output. */
+uint64_t hb_ref_sm_next(uint64_t *state)
+{
+    *state += GAMMA;
+    return hb_ref_mix64(*state);
+}
+
+/* SM(s)[j]: the j-th (0-based) output of a generator whose state starts at s.
+ * After j+1 steps the state is s + (j+1)*GAMMA, so the output can be indexed. */
+uint64_t hb_ref_sm(uint64_t s, uint64_t j)
+{
+    return hb_ref_mix64(s + (j + 1) * GAMMA);
+}
+
+uint64_t hb_ref_tensor_seed(uint64_t root_seed, uint64_t tensor_id)
+{
+    return hb_ref_sm(root_seed, 2 + tensor_id);
+}
+
+/* ------------------------------------------------------------------ */
+/* Shape of the protocol for one (k, m).                               */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    int k, m, w;        /* slice [k, m), width w                               */
+    int R;              /* prefix rounds: 0 if w == 1 else ceil(log2 w)        */
+    int L;              /* w-bit fields per 64-bit dealer word                 */
+    uint64_t Wg;        /* dealer words per group of L elements                */
+    uint64_t mask;      /* 2^w - 1                                             */
+    uint64_t ring;      /* 2^N - 1                                             */
+    uint64_t seedB;     /* binary-material stream   B[j] = SM(seedB)[j]        */
+    uint64_t seedA;     /* arithmetic-material stream A[j] = SM(seedA)[j]      */
+} shape_t;
+
+static int rounds_for(int w)
+{
+    int R = 0;
+    while ((1 << R) < w) R++;
+    return R;
+}
+
+static int make_shape(shape_t *s, int k, int m, uint64_t seed, int ring_bits)
+{
+    if (ring_bits < 1 || ring_bits > 64) return HB_REF_EINVAL;
+    if (k < 0 || m <= k || m > ring_bits) return HB_REF_EINVAL;
+    s->k = k;
+    s->m = m;
+    s->w = m - k;
+    s->R = rounds_for(s->w);
+    s->L = 64 / s->w;
+    if (s->L > 32) s->L = 32;
+    s->Wg = (uint64_t)(5 * (1 + 2 * s->R) + 1);
+    s->mask = (s->w == 64) ? ~0ULL : ((1ULL << s->w) - 1);
+    s->ring = (ring_bits == 64) ? ~0ULL : ((1ULL << ring_bits) - 1);
+    s->seedB = hb_ref_sm(seed, 0);
+    s->seedA = hb_ref_sm(seed, 1);
+    return HB_REF_OK;
+}
+
+/* Opened (publicly reconstructed) bits: gate 0 opens 2w, every prefix round
+ * opens 4w (two AND gates), B2A opens 1, the multiply opens two ring elements
+ * (counted as 128 on the 64-bit production ring). */
+uint64_t hb_ref_opened_bits(int relu, int k, int m, uint64_t n)
+{
+    if (k < 0 || m <= k || m > 64) return 0;
+    uint64_t w = (uint64_t)(m - k);
+    uint64_t R = (uint64_t)rounds_for((int)w);
+    uint64_t per = 2 * w * (1 + 2 * R) + 1;
+    if (relu) per += 128;
+    return n * per;
+}
+
+/* ------------------------------------------------------------------ */
+/* One AND gate on XOR shares through a Beaver triple.                  */
+/* U is masked by a, V is masked by b; d and e are opened.              */
+/* ------------------------------------------------------------------ */
+
+void hb_ref_and_gate(uint64_t U0, uint64_t U1, uint64_t V0, uint64_t V1,
+                     uint64_t a0, uint64_t a1, uint64_t b0, uint64_t b1,
+                     uint64_t c0, uint64_t mask, uint64_t *Z0, uint64_t *Z1)
+{
+    uint64_t c1 = (((a0 ^ a1) & (b0 ^ b1)) ^ c0) & mask;
+    uint64_t d = (U0 ^ a0 ^ U1 ^ a1) & mask;
+    uint64_t e = (V0 ^ b0 ^ V1 ^ b1) & mask;
+    *Z0 = (c0 ^ (d & b0) ^ (e & a0) ^ (d & e)) & mask;
+    *Z1 = (c1 ^ (d & b1) ^ (e & a1)) & mask;
+}
+
+/* ------------------------------------------------------------------ */
+/* One element, start to finish.                                        */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+    uint64_t u[2];      /* sliced shares on Z_2^w                         */
+    uint64_t sum[2];    /* XOR shares of (u0 + u1) mod 2^w, all w bits    */
+    uint64_t sign[2];   /* XOR shares of the MSB of that sum              */
+    uint64_t drelu[2];  /* arithmetic shares of 1 - sign on Z_2^N         */
+    uint64_t relu[2];   /* arithmetic shares of x * (1 - sign) on Z_2^N   */
+} elem_t;
+
+static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
+                         int want_relu, elem_t *t)
+{
+    const uint64_t mask = s->mask, ring = s->ring;
+    const int w = s->w;
+    const uint64_t g = i / (uint64_t)s->L;        /* group                     */
+    const unsigned j = (unsigned)(i % (uint64_t)s->L); /* field inside the group */
+    const unsigned fsh = j * (unsigned)w;         /* field position in a word  */
+    const uint64_t base = g * s->Wg;              /* first dealer word of group */
+    int p, r;
+
+    x0 &= ring;
+    x1 &= ring;
+
+    /* slice: logical shift of the two's-complement pattern, keep w bits */
+    t->u[0] = (x0 >> s->k) & mask;
+    t->u[1] = (x1 >> s->k) & mask;
+
+    /* each party binary-shares its own slice: X = (u0, 0), Y = (0, u1) */
+    uint64_t X[2] = { t->u[0], 0 };
+    uint64_t Y[2] = { 0, t->u[1] };
+    uint64_t P[2], S[2], G[2];
+
+    for (p = 0; p < 2; p++) {
+        P[p] = X[p] ^ Y[p];
+        S[p] = P[p];
+    }
+
+#define FIELD(q, slot) ((hb_ref_sm(s->seedB, base + 5u * (uint64_t)(q) + (slot)) >> fsh) & mask)
+#define AND_GATE(q, U, V, Z) \
+    hb_ref_and_gate((U)[0], (U)[1], (V)[0], (V)[1], FIELD(q, 0), FIELD(q, 1), \
+                    FIELD(q, 2), FIELD(q, 3), FIELD(q, 4), mask, &(Z)[0], &(Z)[1])
+
+    /* gate 0: generate = X AND Y */
+    AND_GATE(0, X, Y, G);
+
+    /* Kogge-Stone prefix rounds, zeros shifted in, both gates use the old P */
+    for (r = 0; r < s->R; r++) {
+        const int sh = 1 << r;
+        uint64_t Gs[2], Ps[2], T[2], Pn[2];
+        for (p = 0; p < 2; p++) {
+            Gs[p] = (G[p] << sh) & mask;
+            Ps[p] = (P[p] << sh) & mask;
+        }
+        AND_GATE(1 + 2 * r, P, Gs, T);
+        AND_GATE(2 + 2 * r, P, Ps, Pn);
+        for (p = 0; p < 2; p++) {
+            G[p] ^= T[p];
+            P[p] = Pn[p];
+        }
+    }
+#undef AND_GATE
+#undef FIELD
+
+    /* sum bit i = propagate_i XOR carry into i; carry into i = G[i-1] */
+    for (p = 0; p < 2; p++) {
+        t->sum[p] = S[p] ^ ((G[p] << 1) & mask);
+        t->sign[p] = (t->sum[p] >> (w - 1)) & 1;
+    }
+
+    /* B2A with one dealer bit r = rho0 ^ rho1, shared both ways */
+    const uint64_t Wb = hb_ref_sm(s->seedB, base + 5u * (uint64_t)(1 + 2 * s->R));
+    const uint64_t rho0 = (Wb >> (2 * j)) & 1;
+    const uint64_t rho1 = (Wb >> (2 * j + 1)) & 1;
+    const uint64_t rbit = rho0 ^ rho1;
+    const uint64_t z = t->sign[0] ^ rho0 ^ t->sign[1] ^ rho1;    /* opened */
+    uint64_t rA[2], beta[2];
+    rA[0] = hb_ref_sm(s->seedA, 6 * i) & ring;
+    rA[1] = (rbit - rA[0]) & ring;
+    /* sign = z XOR r = z + r - 2 z r ; party 0 adds the public z */
+    beta[0] = (rA[0] + z - 2 * z * rA[0]) & ring;
+    beta[1] = (rA[1] - 2 * z * rA[1]) & ring;
+    t->drelu[0] = (1 - beta[0]) & ring;
+    t->drelu[1] = (0 - beta[1]) & ring;
+
+    t->relu[0] = t->relu[1] = 0;
+    if (!want_relu) return;
+
+    /* Beaver multiply x * DReLU on Z_2^N */
+    const uint64_t a0 = hb_ref_sm(s->seedA, 6 * i + 1) & ring;
+    const uint64_t a1 = hb_ref_sm(s->seedA, 6 * i + 2) & ring;
+    const uint64_t b0 = hb_ref_sm(s->seedA, 6 * i + 3) & ring;
+    const uint64_t b1 = hb_ref_sm(s->seedA, 6 * i + 4) & ring;
+    const uint64_t c0 = hb_ref_sm(s->seedA, 6 * i + 5) & ring;
+    const uint64_t c1 = ((a0 + a1) * (b0 + b1) - c0) & ring;
+    const uint64_t eps = ((x0 - a0) + (x1 - a1)) & ring;                       /* opened */
+    const uint64_t del = ((t->drelu[0] - b0) + (t->drelu[1] - b1)) & ring;     /* opened */
+    t->relu[0] = (c0 + eps * b0 + del * a0 + eps * del) & ring;
+    t->relu[1] = (c1 + eps * b1 + del * a1) & ring;
+}
+
+/* ------------------------------------------------------------------ */
+/* Array entry points (host pointers).                                  */
+/* ------------------------------------------------------------------ */
+
+/* Elements first .. first+n-1 of a tensor; share0/share1/out0/out1 point at
+ * element `first`.  what: 0 = DReLU shares, 1 = ReLU shares,
+ * 2 = XOR shares of the full w-bit adder sum, 3 = XOR shares of the sign bit,
+ * 4 = the sliced shares u0, u1. */
+int hb_ref_eval_range(const int64_t *share0, const int64_t *share1, uint64_t first, uint64_t n,
+                      int k, int m, uint64_t seed, int ring_bits, int what,
+                      int64_t *out0, int64_t *out1)
+{
+    shape_t s;
+    uint64_t i;
+    if (what < 0 || what > 4) return HB_REF_EINVAL;
+    if (make_shape(&s, k, m, seed, ring_bits) != HB_REF_OK) return HB_REF_EINVAL;
+    if (n > 0 && (!share0 || !share1 || !out0 || !out1)) return HB_REF_EINVAL;
+    for (i = 0; i < n; i++) {
+        elem_t t;
+        eval_element(&s, first + i, (uint64_t)share0[i], (uint64_t)share1[i], what == 1, &t);
+        const uint64_t *src = what == 0 ? t.drelu : what == 1 ? t.relu : what == 2 ? t.sum
+                              : what == 3 ? t.sign : t.u;
+        out0[i] = (int64_t)src[0];
+        out1[i] = (int64_t)src[1];
+    }
+    return HB_REF_OK;
+}
+
+/* Scattered elements: element index[i] of the tensor carries the share values
+ * share0[i], share1[i].  Same `what` codes as above. */
+int hb_ref_eval_at(const int64_t *share0, const int64_t *share1, const uint64_t *index, uint64_t count,
+                   int k, int m, uint64_t seed, int ring_bits, int what,
+                   int64_t *out0, int64_t *out1)
+{
+    shape_t s;
+    uint64_t i;
+    if (what < 0 || what > 4) return HB_REF_EINVAL;
+    if (make_shape(&s, k, m, seed, ring_bits) != HB_REF_OK) return HB_REF_EINVAL;
+    if (count > 0 && (!share0 || !share1 || !index || !out0 || !out1)) return HB_REF_EINVAL;
+    for (i = 0; i < count; i++) {
+        elem_t t;
+        eval_element(&s, index[i], (uint64_t)share0[i], (uint64_t)share1[i], what == 1, &t);
+        const uint64_t *src = what == 0 ? t.drelu : what == 1 ? t.relu : what == 2 ? t.sum
+                              : what == 3 ? t.sign : t.u;
+        out0[i] = (int64_t)src[0];
+        out1[i] = (int64_t)src[1];
+    }
+    return HB_REF_OK;
+}
+
+int hb_ref_drelu(const int64_t *share0, const int64_t *share1, uint64_t n, int k, int m,
+                 uint64_t seed, int ring_bits, int64_t *out0, int64_t *out1, uint64_t *opened_bits)
+{
+    int st = hb_ref_eval_range(share0, share1, 0, n, k, m, seed, ring_bits, 0, out0, out1);
+    if (st == HB_REF_OK && opened_bits) *opened_bits = hb_ref_opened_bits(0, k, m, n);
+    return st;
+}
+
+int hb_ref_relu(const int64_t *share0, const int64_t *share1, uint64_t n, int k, int m,
+                uint64_t seed, int ring_bits, int64_t *out0, int64_t *out1, uint64_t *opened_bits)
+{
+    int st = hb_ref_eval_range(share0, share1, 0, n, k, m, seed, ring_bits, 1, out0, out1);
+    if (st == HB_REF_OK && opened_bits) *opened_bits = hb_ref_opened_bits(1, k, m, n);
+    return st;
+}
+
+/* Reconstruction: sum of the shares mod 2^N, or their XOR. */
+int hb_ref_open(const int64_t *share0, const int64_t *share1, uint64_t n, int binary,
+                int ring_bits, int64_t *out)
+{
+    uint64_t i, ring;
+    if (ring_bits < 1 || ring_bits > 64) return HB_REF_EINVAL;
+    if (n > 0 && (!share0 || !share1 || !out)) return HB_REF_EINVAL;
+    ring = (ring_bits == 64) ? ~0ULL : ((1ULL << ring_bits) - 1);
+    for (i = 0; i < n; i++) {
+        uint64_t a = (uint64_t)share0[i], b = (uint64_t)share1[i];
+        out[i] = (int64_t)((binary ? (a ^ b) : (a + b)) & ring);
+    }
+    return HB_REF_OK;
+}
