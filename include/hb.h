@@ -1,0 +1,105 @@
+/*
+ * hb.h -- C ABI of the reduced-ring secret-shared DReLU / ReLU library for MI355X (gfx950).
+ *
+ * The operation (paper: "Approximating ReLU on a Reduced Ring for Efficient MPC-based Private
+ * Inference"): a tensor x is held as two additive shares on Z_2^64, x = share0 + share1 (mod 2^64),
+ * in 2^16 fixed point.  ReLU(x) = x * DReLU(x) (Eq. 1, Eq. 2), and DReLU is evaluated on the slice
+ * of bits [k, m) of each share only (Eq. 3; correctness: Sec. 3.1, Theorems 1 and 2):
+ *   slice -> arithmetic-to-binary conversion of the two w-bit slices by an adder circuit on XOR
+ *   shares whose AND gates consume Beaver triples (Sec. 2.2 "Evaluating ReLU with GMW") -> the most
+ *   significant bit is the sign -> binary-to-arithmetic conversion of that one bit, 1 - sign ->
+ *   Beaver multiplication with the full 64-bit share.
+ * Both parties are evaluated inside one kernel (like the paper's single-node simulator, Sec. 4.1.1);
+ * openings are register XOR / add.  All dealer material (AND triples, the B2A bit, the multiply
+ * triple) is drawn inside the kernel from two SplitMix64 streams keyed by `seed`.
+ *
+ * Conventions for every entry point
+ *   - (k, m): lowest kept bit, one past the highest kept bit; valid iff 0 <= k < m <= 64; w = m - k.
+ *     (The paper writes this slice x[m:k]: its letters are the other way round.)
+ *   - share0, share1, out0, out1, out: DEVICE pointers to n contiguous int64, owned by the caller,
+ *     8-byte aligned (16-byte aligned buffers take vector loads).  An output may be the very same
+ *     buffer as an input (in place); any other overlap between an output and another buffer of the
+ *     call is rejected.
+ *   - stream: a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on that
+ *     stream; the call does not synchronise, does not allocate and keeps no state between calls.
+ *   - opened_bits: HOST pointer or NULL; receives the number of bits the two parties would open to
+ *     each other for this call (closed form, written before the call returns).
+ *   - return value: HB_OK or a negative status; on error nothing is enqueued and no output is
+ *     written.  n == 0 is a successful no-op (arguments are still validated).
+ *   - results depend only on (inputs, k, m, seed): the same call twice gives the same shares, and
+ *     a tensor may be processed in pieces only through the whole-tensor entry points (element i's
+ *     dealer material is indexed by i).
+ */
+#ifndef HB_H
+#define HB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HB_API __attribute__((visibility("default")))
+
+enum hb_status {
+    HB_OK = 0,
+    HB_EINVAL = -1, /* null pointer with n > 0, bad (k, m), n too large, forbidden overlap, not device memory */
+    HB_EALIGN = -2, /* a pointer is not 8-byte aligned */
+    HB_EHIP = -3    /* the HIP runtime refused the launch; hb_last_hip_error() names the reason */
+};
+
+/* Largest n accepted by one call (2^40 elements). */
+#define HB_MAX_ELEMENTS ((size_t)1 << 40)
+
+/*
+ * DReLU (Sec. 2.2; reduced ring: Eq. 3 without the final product).
+ * out0[i] + out1[i] = 1 - MSB_w((u0 + u1) mod 2^w) (mod 2^64), u_p = (share_p[i] >> k) mod 2^w:
+ * arithmetic shares on Z_2^64 of 1 when the w-bit window of x reads as non-negative, else 0.
+ */
+HB_API int hb_drelu(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed,
+             int64_t *out0, int64_t *out1, uint64_t *opened_bits, void *stream);
+
+/*
+ * Approximate ReLU (Eq. 3): out0[i] + out1[i] = (share0[i] + share1[i]) * DReLU (mod 2^64), where
+ * DReLU is exactly what hb_drelu returns for the same (inputs, k, m, seed).
+ */
+HB_API int hb_relu(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed,
+            int64_t *out0, int64_t *out1, uint64_t *opened_bits, void *stream);
+
+/*
+ * The binary half alone (Sec. 2.2: A2B by the adder circuit, sign = most significant bit):
+ * out0[i] ^ out1[i] = MSB_w((u0 + u1) mod 2^w); each out_p[i] is 0 or 1 and is party p's XOR share
+ * of the sign as it stands after the last prefix round, before B2A.  Same dealer material as
+ * hb_drelu / hb_relu.  opened_bits receives n * 2w(1 + 2R) (the circuit's openings only).
+ */
+HB_API int hb_sign_shares(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed,
+                   int64_t *out0, int64_t *out1, uint64_t *opened_bits, void *stream);
+
+/*
+ * Reconstruction (Sec. 2.2 "Notations"): out[i] = share0[i] + share1[i] (mod 2^64) when binary == 0,
+ * share0[i] ^ share1[i] otherwise.  `out` may be one of the inputs.
+ */
+HB_API int hb_open(const int64_t *share0, const int64_t *share1, size_t n, int binary, int64_t *out, void *stream);
+
+/* Seed of tensor `tensor_id` in a set of tensors keyed by one root seed (host-only, no GPU work). */
+HB_API uint64_t hb_tensor_seed(uint64_t root_seed, uint64_t tensor_id);
+
+/*
+ * Bits opened for n elements: n * (2w(1 + 2R) + 1) for DReLU (relu == 0), plus 128 n for ReLU
+ * (relu != 0); R = 0 if w == 1 else ceil(log2 w) rounds (Sec. 4.2).  The unpacked 64-bit baseline
+ * of Sec. 2.3 is 29 * 64 = 1856 bits per element.  Returns 0 for an invalid (k, m).
+ */
+HB_API uint64_t hb_opened_bits(int relu, int k, int m, size_t n);
+
+/* Static description of a status code. */
+HB_API const char *hb_strerror(int status);
+
+/* Text of the HIP error behind the calling thread's most recent HB_EHIP ("" if none). */
+HB_API const char *hb_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* HB_H */

@@ -1,0 +1,204 @@
+// C ABI of the library (include/hb.h): argument checks on the host, closed-form opened-bit counts,
+// kernel selection by slice width, launch on the caller's stream.  No allocation, no synchronisation.
+#include "../../include/hb.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <utility>
+
+#include "hb_kernels.hpp"
+#include "hb_launch.hpp"
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int fail_hip(hipError_t e, const char *what)
+{
+    std::snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+    (void)hipGetLastError();
+    return HB_EHIP;
+}
+
+bool valid_slice(int k, int m) { return k >= 0 && m > k && m <= 64; }
+
+int rounds_of(int w) { return hb::ceil_log2(w); }
+
+struct Range {
+    uintptr_t lo, hi;
+};
+
+Range range_of(const void *p, size_t n) { return Range{(uintptr_t)p, (uintptr_t)p + n * sizeof(int64_t)}; }
+
+bool same(Range a, Range b) { return a.lo == b.lo; }
+bool disjoint(Range a, Range b) { return a.hi <= b.lo || b.hi <= a.lo; }
+
+// The buffer must be memory the GPU can address, and [p, p + 8n) must lie inside one allocation.
+int check_device_buffer(const void *p, size_t n)
+{
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return HB_EINVAL;  // not known to the HIP runtime: plain host memory or a wild pointer
+    }
+    switch (attr.type) {
+    case hipMemoryTypeDevice:
+    case hipMemoryTypeManaged:
+        break;
+    case hipMemoryTypeHost:  // pinned host memory is usable only through its device-side address
+        if (attr.devicePointer != p) return HB_EINVAL;
+        break;
+    default:  // unregistered host memory, arrays
+        return HB_EINVAL;
+    }
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    e = hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return HB_OK;  // allocation kinds without a queryable range: the attribute check has passed
+    }
+    const uintptr_t lo = (uintptr_t)base, hi = lo + size;
+    const Range r = range_of(p, n);
+    return (r.lo >= lo && r.hi <= hi) ? HB_OK : HB_EINVAL;
+}
+
+int check_common(const void *const *ptrs, int count, size_t n)
+{
+    if (n > HB_MAX_ELEMENTS) return HB_EINVAL;
+    if (n == 0) return HB_OK;
+    for (int i = 0; i < count; ++i) {
+        if (ptrs[i] == nullptr) return HB_EINVAL;
+    }
+    for (int i = 0; i < count; ++i) {
+        if (((uintptr_t)ptrs[i] & 7u) != 0) return HB_EALIGN;
+    }
+    for (int i = 0; i < count; ++i) {
+        const int st = check_device_buffer(ptrs[i], n);
+        if (st != HB_OK) return st;
+    }
+    return HB_OK;
+}
+
+bool all_aligned16(const void *const *ptrs, int count)
+{
+    for (int i = 0; i < count; ++i) {
+        if (((uintptr_t)ptrs[i] & 15u) != 0) return false;
+    }
+    return true;
+}
+
+int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
+        int64_t *out1, uint64_t *opened_bits, void *stream)
+{
+    if (!valid_slice(k, m)) return HB_EINVAL;
+    const void *ptrs[4] = {share0, share1, out0, out1};
+    const int st = check_common(ptrs, 4, n);
+    if (st != HB_OK) return st;
+    const int w = m - k;
+    if (n > 0) {
+        const Range i0 = range_of(share0, n), i1 = range_of(share1, n), r0 = range_of(out0, n), r1 = range_of(out1, n);
+        // an output may coincide with an input; every other overlap is refused
+        if (!disjoint(r0, r1)) return HB_EINVAL;
+        if (!(same(r0, i0) || disjoint(r0, i0)) || !(same(r0, i1) || disjoint(r0, i1))) return HB_EINVAL;
+        if (!(same(r1, i0) || disjoint(r1, i0)) || !(same(r1, i1) || disjoint(r1, i1))) return HB_EINVAL;
+    }
+    uint64_t bits = 0;
+    if (mode == hb::kSign) {
+        bits = (uint64_t)n * (2ull * (uint64_t)w * (1 + 2 * (uint64_t)rounds_of(w)));
+    } else {
+        bits = hb_opened_bits(mode == hb::kRelu, k, m, n);
+    }
+    if (n > 0) {
+        const uint64_t seedB = hb::stream_word(seed, 0), seedA = hb::stream_word(seed, 1);
+        const hb::GroupLauncher f = hb::launcher_table().f[mode][w - 1];
+        if (f == nullptr) return fail_hip(hipErrorInvalidDeviceFunction, "no kernel was built for this slice width");
+        const hipError_t e = f((const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, k, seedB, seedA,
+                               (uint64_t *)out0, (uint64_t *)out1, all_aligned16(ptrs, 4), (hipStream_t)stream);
+        if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    }
+    if (opened_bits) *opened_bits = bits;
+    return HB_OK;
+}
+
+}  // namespace
+
+namespace hb {
+LauncherTable &launcher_table()
+{
+    static LauncherTable table = {};
+    return table;
+}
+}  // namespace hb
+
+extern "C" {
+
+int hb_drelu(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
+             int64_t *out1, uint64_t *opened_bits, void *stream)
+{
+    return run(hb::kDrelu, share0, share1, n, k, m, seed, out0, out1, opened_bits, stream);
+}
+
+int hb_relu(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
+            int64_t *out1, uint64_t *opened_bits, void *stream)
+{
+    return run(hb::kRelu, share0, share1, n, k, m, seed, out0, out1, opened_bits, stream);
+}
+
+int hb_sign_shares(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
+                   int64_t *out1, uint64_t *opened_bits, void *stream)
+{
+    return run(hb::kSign, share0, share1, n, k, m, seed, out0, out1, opened_bits, stream);
+}
+
+int hb_open(const int64_t *share0, const int64_t *share1, size_t n, int binary, int64_t *out, void *stream)
+{
+    const void *ptrs[3] = {share0, share1, out};
+    const int st = check_common(ptrs, 3, n);
+    if (st != HB_OK) return st;
+    if (n == 0) return HB_OK;
+    const Range i0 = range_of(share0, n), i1 = range_of(share1, n), r = range_of(out, n);
+    if (!(same(r, i0) || disjoint(r, i0)) || !(same(r, i1) || disjoint(r, i1))) return HB_EINVAL;
+    const bool vec = all_aligned16(ptrs, 3);
+    const uint64_t threads = vec ? ((uint64_t)n + 1) / 2 : (uint64_t)n;
+    const uint64_t blocks = (threads + hb::kBlock - 1) / hb::kBlock;
+    if (blocks > 0x7fffffffull) return HB_EINVAL;
+    if (vec) {
+        hipLaunchKernelGGL((hb::open_kernel<true>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, (hipStream_t)stream,
+                           (const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, binary, (uint64_t *)out);
+    } else {
+        hipLaunchKernelGGL((hb::open_kernel<false>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, (hipStream_t)stream,
+                           (const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, binary, (uint64_t *)out);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return HB_OK;
+}
+
+uint64_t hb_tensor_seed(uint64_t root_seed, uint64_t tensor_id) { return hb::stream_word(root_seed, 2 + tensor_id); }
+
+uint64_t hb_opened_bits(int relu, int k, int m, size_t n)
+{
+    if (!valid_slice(k, m)) return 0;
+    const uint64_t w = (uint64_t)(m - k);
+    const uint64_t per = 2 * w * (1 + 2 * (uint64_t)rounds_of((int)w)) + 1 + (relu ? 128 : 0);
+    return (uint64_t)n * per;
+}
+
+const char *hb_strerror(int status)
+{
+    switch (status) {
+    case HB_OK: return "success";
+    case HB_EINVAL: return "invalid argument (null pointer, bad (k, m), size, overlap, or not device memory)";
+    case HB_EALIGN: return "pointer is not 8-byte aligned";
+    case HB_EHIP: return "HIP runtime error (see hb_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+const char *hb_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,20 @@
+// Table of kernel launchers indexed by (mode, slice width).  The kernels are instantiated in several
+// translation units (hb_launch_part.hip compiled once per mode and width range) that register
+// themselves here when the library is loaded.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hb {
+
+using GroupLauncher = hipError_t (*)(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t seedB,
+                                     uint64_t seedA, uint64_t *o0, uint64_t *o1, bool vec16, hipStream_t stream);
+
+struct LauncherTable {
+    GroupLauncher f[3][64];   // [mode][w - 1]
+};
+
+LauncherTable &launcher_table();
+
+}  // namespace hb

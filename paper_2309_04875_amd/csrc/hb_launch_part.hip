@@ -1,0 +1,42 @@
+// Instantiates the group kernels of one mode for slice widths HB_PART_LO..HB_PART_HI and registers
+// their launchers.  Compiled several times with different -D values so the parts build in parallel.
+#include "hb_kernels.hpp"
+#include "hb_launch.hpp"
+
+#if !defined(HB_PART_MODE) || !defined(HB_PART_LO) || !defined(HB_PART_HI)
+#error "compile with -DHB_PART_MODE=<0|1|2> -DHB_PART_LO=<w> -DHB_PART_HI=<w>"
+#endif
+
+namespace {
+
+template <int W, int MODE>
+hipError_t launch_group(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
+                        uint64_t *o0, uint64_t *o1, bool vec16, hipStream_t stream)
+{
+    constexpr uint64_t L = hb::Shape<W>::L;
+    const uint64_t groups = (n + L - 1) / L;
+    const uint64_t blocks = (groups + hb::kBlock - 1) / hb::kBlock;
+    if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    if (vec16) {
+        hipLaunchKernelGGL((hb::group_kernel<W, MODE, true>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, stream, x0,
+                           x1, n, groups, k, seedB, seedA, o0, o1);
+    } else {
+        hipLaunchKernelGGL((hb::group_kernel<W, MODE, false>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, stream, x0,
+                           x1, n, groups, k, seedB, seedA, o0, o1);
+    }
+    return hipGetLastError();
+}
+
+template <int W>
+void fill(hb::LauncherTable &t)
+{
+    t.f[HB_PART_MODE][W - 1] = &launch_group<W, HB_PART_MODE>;
+    if constexpr (W < HB_PART_HI) fill<W + 1>(t);
+}
+
+struct Registrar {
+    Registrar() { fill<HB_PART_LO>(hb::launcher_table()); }
+};
+const Registrar g_registrar;
+
+}  // namespace

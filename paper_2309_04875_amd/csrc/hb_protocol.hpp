@@ -1,0 +1,164 @@
+// Device-side statement of the protocol, in SWAR form: L = min(64/W, 32) elements share one 64-bit word,
+// element j of a group occupying bits [jW, jW+W).  Every step below is bitwise, so the L fields never
+// interact except through shifts, which are confined to their field by a mask.
+//
+// Paper: Sec. 2.2 "Evaluating ReLU with GMW" (A2B adder on XOR shares, Beaver AND, sign, B2A),
+// Eq. 3 (DReLU on the slice only), Sec. 4.2 (depth ceil(log2 w), packing of w-bit fields in 64-bit words).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hb {
+
+// ---- dealer streams: SplitMix64, output j of a generator started at state s is mix(s + (j+1)*gamma)
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__host__ __device__ __forceinline__ uint64_t stream_word(uint64_t s, uint64_t j)
+{
+    return mix64(s + (j + 1) * kGamma);
+}
+
+// ---- compile-time shape of the circuit for slice width W
+constexpr int ceil_log2(int w)
+{
+    int r = 0;
+    while ((1 << r) < w) ++r;
+    return r;
+}
+
+template <int W>
+struct Shape {
+    static_assert(W >= 1 && W <= 64, "slice width");
+    static constexpr int w = W;
+    static constexpr int R = ceil_log2(W);                     // prefix rounds (0 when W == 1)
+    static constexpr int L = (64 / W) > 32 ? 32 : (64 / W);     // fields per word
+    static constexpr int kGates = 1 + 2 * R;                    // gate 0 + two per round
+    static constexpr int kWordsPerGroup = 5 * kGates + 1;       // five triple words per gate + the B2A word
+    static constexpr uint64_t kField = (W == 64) ? ~0ull : ((1ull << (W & 63)) - 1);
+
+    // bit 0 of every field
+    static constexpr uint64_t ones()
+    {
+        uint64_t r = 0;
+        for (int j = 0; j < L; ++j) r |= 1ull << (j * W);
+        return r;
+    }
+    // positions of a word that still hold data of their own field after a left shift by s
+    static constexpr uint64_t keep(int s)
+    {
+        uint64_t f = (s >= W) ? 0 : ((kField << s) & kField);
+        uint64_t r = 0;
+        for (int j = 0; j < L; ++j) r |= f << (j * W);
+        return r;
+    }
+};
+
+struct Pair {      // one value held as (party 0 share, party 1 share)
+    uint64_t p0, p1;
+};
+
+// One Beaver AND on XOR-shared words.  zq is the generator state of the gate's first dealer word
+// (word a_0); the five words a_0 a_1 b_0 b_1 c_0 are consecutive outputs.  U is masked by a, V by b;
+// d and e are the opened words; party 0 takes the public d&e term.
+__device__ __forceinline__ Pair beaver_and(uint64_t zq, Pair U, Pair V)
+{
+    const uint64_t a0 = mix64(zq);
+    const uint64_t a1 = mix64(zq + 1 * kGamma);
+    const uint64_t b0 = mix64(zq + 2 * kGamma);
+    const uint64_t b1 = mix64(zq + 3 * kGamma);
+    const uint64_t c0 = mix64(zq + 4 * kGamma);
+    const uint64_t c1 = ((a0 ^ a1) & (b0 ^ b1)) ^ c0;           // dealer completes the triple
+    const uint64_t d = (U.p0 ^ a0) ^ (U.p1 ^ a1);               // each party sends U_p ^ a_p
+    const uint64_t e = (V.p0 ^ b0) ^ (V.p1 ^ b1);
+    Pair Z;
+    Z.p0 = c0 ^ (d & b0) ^ (e & a0) ^ (d & e);
+    Z.p1 = c1 ^ (d & b1) ^ (e & a1);
+    return Z;
+}
+
+// A2B + sign for one group.  u0/u1: the L sliced shares of party 0 / party 1 packed as fields.
+// zg: generator state of the group's first dealer word.  Returns XOR shares of the sum word
+// S ^ (G << 1); the sign of field j is bit jW + W - 1.  The last round's P-update gate is not
+// evaluated: nothing reads its result (its dealer words are simply never drawn).
+template <int W>
+__device__ __forceinline__ Pair a2b_sum(uint64_t u0, uint64_t u1, uint64_t zg)
+{
+    using S = Shape<W>;
+    // X = (u0, 0), Y = (0, u1): each party XOR-shares its own slice trivially
+    const Pair X{u0, 0}, Y{0, u1};
+    Pair P{X.p0 ^ Y.p0, X.p1 ^ Y.p1};
+    const Pair Sum = P;
+    Pair G = beaver_and(zg, X, Y);
+#pragma unroll
+    for (int r = 0; r < S::R; ++r) {
+        const int s = 1 << r;
+        const uint64_t keep = S::keep(s);
+        const Pair Gs{(G.p0 << s) & keep, (G.p1 << s) & keep};
+        const Pair T = beaver_and(zg + (uint64_t)(5 * (1 + 2 * r)) * kGamma, P, Gs);
+        if (r + 1 < S::R) {
+            const Pair Ps{(P.p0 << s) & keep, (P.p1 << s) & keep};
+            P = beaver_and(zg + (uint64_t)(5 * (2 + 2 * r)) * kGamma, P, Ps);
+        }
+        G.p0 ^= T.p0;
+        G.p1 ^= T.p1;
+    }
+    const uint64_t keep1 = S::keep(1);
+    return Pair{Sum.p0 ^ ((G.p0 << 1) & keep1), Sum.p1 ^ ((G.p1 << 1) & keep1)};
+}
+
+// B2A of the sign bit and 1 - sign, for one element.  sign/rho: XOR shares of the sign and of the
+// dealer bit r.  zA: generator state of the element's first arithmetic word A[6i].
+__device__ __forceinline__ Pair b2a_drelu(Pair sign, Pair rho, uint64_t zA)
+{
+    const uint64_t z = (sign.p0 ^ rho.p0) ^ (sign.p1 ^ rho.p1);   // opened bit
+    const uint64_t r = rho.p0 ^ rho.p1;                           // known to the dealer only
+    const uint64_t rA0 = mix64(zA);
+    const uint64_t rA1 = r - rA0;
+    // sign = z ^ r = z + r - 2zr; party 0 adds the public z
+    const uint64_t beta0 = z ? (1 - rA0) : rA0;
+    const uint64_t beta1 = z ? (0 - rA1) : rA1;
+    return Pair{1 - beta0, 0 - beta1};
+}
+
+// Beaver multiply x * D on Z_2^64 for one element; the triple is A[6i+1 .. 6i+5].
+__device__ __forceinline__ Pair beaver_mul(Pair x, Pair D, uint64_t zA)
+{
+    const uint64_t a0 = mix64(zA + 1 * kGamma);
+    const uint64_t a1 = mix64(zA + 2 * kGamma);
+    const uint64_t b0 = mix64(zA + 3 * kGamma);
+    const uint64_t b1 = mix64(zA + 4 * kGamma);
+    const uint64_t c0 = mix64(zA + 5 * kGamma);
+    const uint64_t c1 = (a0 + a1) * (b0 + b1) - c0;               // dealer completes the triple
+    const uint64_t eps = (x.p0 - a0) + (x.p1 - a1);               // opened
+    const uint64_t del = (D.p0 - b0) + (D.p1 - b1);               // opened
+    Pair out;
+    out.p0 = c0 + eps * (b0 + del) + del * a0;                    // = c0 + eps*b0 + del*a0 + eps*del
+    out.p1 = c1 + eps * b1 + del * a1;
+    return out;
+}
+
+enum Mode { kDrelu = 0, kRelu = 1, kSign = 2 };
+
+// Everything after the circuit for element j of a group: pick the element's sign and dealer bits
+// out of the group words, B2A, multiply.
+template <int W, int MODE>
+__device__ __forceinline__ Pair finish_element(Pair sum, uint64_t wb, int j, Pair x, uint64_t zA)
+{
+    const int sb = j * W + W - 1;
+    const Pair sign{(sum.p0 >> sb) & 1, (sum.p1 >> sb) & 1};
+    if (MODE == kSign) return sign;
+    const Pair rho{(wb >> (2 * j)) & 1, (wb >> (2 * j + 1)) & 1};
+    const Pair D = b2a_drelu(sign, rho, zA);
+    if (MODE == kDrelu) return D;
+    return beaver_mul(x, D, zA);
+}
+
+}  // namespace hb

@@ -1,0 +1,141 @@
+"""ctypes binding of the C ABI in include/hb.h -- argument marshalling only.
+
+Every function has the name and meaning of its C counterpart; tensors are torch int64 CUDA tensors
+whose `data_ptr()` is handed through, and the stream is torch's current stream unless one is given.
+There is no fallback: if libhb.so has not been built, loading raises.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIBRARY = os.path.join(HERE, "libhb.so")
+
+HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP = 0, -1, -2, -3
+BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accounting
+
+EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_tensor_seed", "hb_opened_bits",
+           "hb_strerror", "hb_last_hip_error")
+
+_lib = None
+
+
+class HbError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("hb status %d: %s" % (status, text))
+        self.status = status
+
+
+def load():
+    """Load libhb.so (once) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIBRARY):
+        raise ImportError("%s is missing: build it with `python -m paper_2309_04875_amd.build` "
+                          "(there is no CPU fallback)" % LIBRARY)
+    lib = ctypes.CDLL(LIBRARY)
+    vp, u64, sz, ci = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_int
+    u64p = ctypes.POINTER(ctypes.c_uint64)
+    for name in ("hb_drelu", "hb_relu", "hb_sign_shares"):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [vp, vp, sz, ci, ci, u64, vp, vp, u64p, vp]
+    lib.hb_open.restype = ci
+    lib.hb_open.argtypes = [vp, vp, sz, ci, vp, vp]
+    lib.hb_tensor_seed.restype = u64
+    lib.hb_tensor_seed.argtypes = [u64, u64]
+    lib.hb_opened_bits.restype = u64
+    lib.hb_opened_bits.argtypes = [ci, ci, ci, sz]
+    lib.hb_strerror.restype = ctypes.c_char_p
+    lib.hb_strerror.argtypes = [ci]
+    lib.hb_last_hip_error.restype = ctypes.c_char_p
+    lib.hb_last_hip_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def strerror(status):
+    return load().hb_strerror(int(status)).decode()
+
+
+def last_hip_error():
+    return load().hb_last_hip_error().decode()
+
+
+def _check(status):
+    if status != HB_OK:
+        text = strerror(status)
+        if status == HB_EHIP:
+            text += ": " + last_hip_error()
+        raise HbError(status, text)
+
+
+def _tensor_args(*tensors):
+    import torch
+    n = tensors[0].numel()
+    for t in tensors:
+        if not isinstance(t, torch.Tensor) or t.dtype != torch.int64 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError("expected contiguous int64 CUDA tensors")
+        if t.numel() != n:
+            raise ValueError("tensors differ in size")
+    return n
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _shares_call(name, share0, share1, k, m, seed, out0, out1, stream):
+    import torch
+    if out0 is None:
+        out0 = torch.empty_like(share0)
+    if out1 is None:
+        out1 = torch.empty_like(share1)
+    n = _tensor_args(share0, share1, out0, out1)
+    bits = ctypes.c_uint64(0)
+    st = getattr(load(), name)(share0.data_ptr(), share1.data_ptr(), n, int(k), int(m), int(seed) & (2**64 - 1),
+                               out0.data_ptr(), out1.data_ptr(), ctypes.byref(bits), _stream_handle(stream))
+    _check(st)
+    return out0, out1, int(bits.value)
+
+
+def hb_drelu(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
+    """Arithmetic shares of DReLU on the slice [k, m); returns (out0, out1, opened_bits)."""
+    return _shares_call("hb_drelu", share0, share1, k, m, seed, out0, out1, stream)
+
+
+def hb_relu(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
+    """Arithmetic shares of x * DReLU; returns (out0, out1, opened_bits)."""
+    return _shares_call("hb_relu", share0, share1, k, m, seed, out0, out1, stream)
+
+
+def hb_sign_shares(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
+    """XOR shares (0/1) of the sign bit after the adder circuit; returns (out0, out1, opened_bits)."""
+    return _shares_call("hb_sign_shares", share0, share1, k, m, seed, out0, out1, stream)
+
+
+def hb_open(share0, share1, binary=False, out=None, stream=None):
+    """share0 + share1 (mod 2^64), or share0 ^ share1 when binary."""
+    import torch
+    if out is None:
+        out = torch.empty_like(share0)
+    n = _tensor_args(share0, share1, out)
+    _check(load().hb_open(share0.data_ptr(), share1.data_ptr(), n, int(bool(binary)), out.data_ptr(),
+                          _stream_handle(stream)))
+    return out
+
+
+def hb_tensor_seed(root_seed, tensor_id):
+    return int(load().hb_tensor_seed(int(root_seed) & (2**64 - 1), int(tensor_id)))
+
+
+def hb_opened_bits(relu, k, m, n):
+    return int(load().hb_opened_bits(int(bool(relu)), int(k), int(m), int(n)))
+
+
+def raw(name, *args):
+    """Call an entry point with raw integers / pointers (tests of the error paths); returns its status."""
+    return getattr(load(), name)(*args)

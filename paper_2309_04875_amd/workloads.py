@@ -132,3 +132,31 @@ def width_sweep(n: int = 1 << 26, seed: int = 4, widths=(64, 32, 16, 8, 6, 4)) -
 def resnet18_imagenet(batch: int = 64, seed: int = 5) -> List[TensorSpec]:
     """17 ReLU inputs of ResNet18 on 3x224x224 images; k in [6,16], w in {6, 8, 10} per tensor."""
     return _per_tensor("resnet18_imagenet_b%d" % batch, RESNET18_224, batch, seed, (6, 16), (6, 8, 10))
+
+
+def materialize_on_device(spec: TensorSpec, device="cuda"):
+    """(x, share0, share1) as flat int64 tensors generated on the GPU with torch's seeded generator.
+
+    Same distributions as `materialize` (different random streams); used where the host generator
+    would dominate the run time (the batch-512 and 224x224 sets, the 2^26 sweep).
+    """
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(spec.data_seed))
+    n = spec.n
+    if spec.dist == "normal":
+        v = torch.randn(n, generator=g, device=device, dtype=torch.float64) * spec.sigma
+    elif spec.dist == "laplace":
+        u = torch.rand(n, generator=g, device=device, dtype=torch.float64) - 0.5
+        v = -spec.sigma * torch.sign(u) * torch.log1p(-2.0 * u.abs())
+        del u
+    else:
+        raise ValueError(spec.dist)
+    x = torch.round(v * SCALE).to(torch.int64)
+    del v
+    hi = torch.randint(0, 1 << 32, (n,), generator=g, device=device, dtype=torch.int64)
+    lo = torch.randint(0, 1 << 32, (n,), generator=g, device=device, dtype=torch.int64)
+    share0 = (hi << 32) | lo
+    del hi, lo
+    share1 = x - share0           # int64 arithmetic wraps mod 2^64
+    return x, share0, share1

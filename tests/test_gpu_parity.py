@@ -1,0 +1,277 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle -- bit for bit.
+
+Everything is integer, so the tolerance is zero: `torch.equal` / `np.array_equal` on int64.
+Small cases are compared element by element over the whole tensor; the full-size workloads are
+compared on sampled elements (the oracle can evaluate any element by its index) plus properties
+that hold for every element and are checked on the device (reconstruction identities).
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2309_04875_amd import hb, workloads
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x2309048750000001
+DEV = "cuda"
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _host(t):
+    return t.cpu().numpy()
+
+
+def _rand_shares(rng, n):
+    return (rng.integers(0, 1 << 64, n, dtype=np.uint64).view(np.int64),
+            rng.integers(0, 1 << 64, n, dtype=np.uint64).view(np.int64))
+
+
+def _check_all_modes(s0, s1, k, m, seed, modes=("relu", "drelu", "sign")):
+    d0, d1 = _dev(s0), _dev(s1)
+    if "relu" in modes:
+        g0, g1, bits = hb.hb_relu(d0, d1, k, m, seed)
+        e0, e1, ebits = oracle.relu(s0, s1, k, m, seed)
+        assert np.array_equal(_host(g0), e0) and np.array_equal(_host(g1), e1), ("relu", k, m)
+        assert bits == ebits
+    if "drelu" in modes:
+        g0, g1, bits = hb.hb_drelu(d0, d1, k, m, seed)
+        e0, e1, ebits = oracle.drelu(s0, s1, k, m, seed)
+        assert np.array_equal(_host(g0), e0) and np.array_equal(_host(g1), e1), ("drelu", k, m)
+        assert bits == ebits
+    if "sign" in modes:
+        g0, g1, _ = hb.hb_sign_shares(d0, d1, k, m, seed)
+        e0, e1 = oracle.evaluate(s0, s1, k, m, seed, oracle.WHAT_SIGN)
+        assert np.array_equal(_host(g0), e0) and np.array_equal(_host(g1), e1), ("sign", k, m)
+
+
+# ----------------------------------------------------------------------------------------------
+# every slice width, several tiles and a ragged tail
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("w", range(1, 65))
+def test_every_width_matches_oracle(w):
+    rng = np.random.default_rng(w)
+    L = min(64 // w, 32)
+    n = 3 * 256 * L + L // 2 + 1           # three full thread blocks of groups and a partial group
+    for k in sorted({0, 64 - w, (64 - w) // 3}):
+        s0, s1 = _rand_shares(rng, n)
+        _check_all_modes(s0, s1, k, k + w, SEED ^ (w * 1315423911))
+
+
+@pytest.mark.parametrize("k,m", [(12, 20), (0, 64), (8, 14), (8, 12), (8, 18), (8, 40), (3, 4)])
+def test_ragged_sizes_and_extremes(k, m):
+    w = m - k
+    L = min(64 // w, 32)
+    i64 = np.iinfo(np.int64)
+    rng = np.random.default_rng(k * 64 + m)
+    for n in sorted({1, 2, L - 1, L, L + 1, 2 * L + 1, 255 * L, 256 * L, 256 * L + 1, 1000}):
+        if n <= 0:
+            continue
+        s0, s1 = _rand_shares(rng, n)
+        ext = np.array([0, -1, i64.min, i64.max, 1, i64.min + 1], dtype=np.int64)
+        c = min(n, ext.size)
+        s0[:c] = ext[:c]
+        s1[:c] = ext[::-1][:c]
+        _check_all_modes(s0, s1, k, m, SEED + n)
+
+
+# ----------------------------------------------------------------------------------------------
+# the named workloads, small enough to compare in full
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("k,m", [(0, 64), (12, 20)])
+def test_flat_normal_65536(k, m):
+    spec = workloads.flat_normal(65536, k, m)
+    x, s0, s1 = workloads.materialize(spec)
+    _check_all_modes(s0, s1, k, m, SEED)
+    d0, d1 = _dev(s0), _dev(s1)
+    r0, r1, _ = hb.hb_relu(d0, d1, k, m, SEED)
+    rec = _host(hb.hb_open(r0, r1))
+    if (k, m) == (0, 64):
+        assert np.array_equal(rec, np.maximum(x, 0))
+    else:
+        ok = (np.abs(x) >= (1 << k)) & (np.abs(x) < (1 << (m - 1)) - (1 << k))
+        assert np.array_equal(rec[ok], np.maximum(x, 0)[ok])
+
+
+def test_resnet18_cifar_one_image_set():
+    root = SEED
+    total_bits = 0
+    for spec in workloads.resnet18_cifar():
+        x, s0, s1 = workloads.materialize(spec)
+        seed = hb.hb_tensor_seed(root, spec.tensor_id)
+        assert seed == oracle.tensor_seed(root, spec.tensor_id)
+        d0, d1 = _dev(s0), _dev(s1)
+        g0, g1, bits = hb.hb_relu(d0, d1, spec.k, spec.m, seed)
+        e0, e1, ebits = oracle.relu(s0, s1, spec.k, spec.m, seed)
+        assert np.array_equal(_host(g0), e0) and np.array_equal(_host(g1), e1), spec
+        assert bits == ebits
+        total_bits += bits
+    assert total_bits == 557056 * 241
+
+
+# ----------------------------------------------------------------------------------------------
+# full-size workloads: sampled elements against the oracle + identities on every element
+# ----------------------------------------------------------------------------------------------
+
+def _closed_form_drelu(s0, s1, k, m):
+    """1 - MSB_w((u0 + u1) mod 2^w) with torch integer ops on the device (int64 wraps mod 2^64)."""
+    w = m - k
+    if w == 64:
+        total = s0 + s1
+        return 1 - ((total >> 63) & 1)
+    mask = (1 << w) - 1
+    u0 = (s0 >> k) & mask
+    u1 = (s1 >> k) & mask
+    return 1 - (((u0 + u1) & mask) >> (w - 1))
+
+
+def _sample_indices(n, L, rng, count):
+    edge = np.concatenate([np.arange(0, min(n, 4 * L)), np.arange(max(0, n - 4 * L), n)])
+    rnd = rng.integers(0, n, count)
+    return np.unique(np.concatenate([edge, rnd])).astype(np.int64)
+
+
+def _check_large(spec, seed, rng, samples=1 << 16, modes=("relu",)):
+    x, s0, s1 = workloads.materialize_on_device(spec, DEV)
+    n, k, m = spec.n, spec.k, spec.m
+    L = min(64 // (m - k), 32)
+    idx = _sample_indices(n, L, rng, samples)
+    tidx = torch.from_numpy(idx).to(DEV)
+    h0, h1 = _host(s0[tidx]), _host(s1[tidx])
+    dexp = _closed_form_drelu(s0, s1, k, m)
+    if "relu" in modes:
+        r0, r1, bits = hb.hb_relu(s0, s1, k, m, seed)
+        assert bits == oracle.opened_bits(True, k, m, n)
+        e0, e1 = oracle.evaluate_at(h0, h1, idx.astype(np.uint64), k, m, seed, oracle.WHAT_RELU)
+        assert np.array_equal(_host(r0[tidx]), e0) and np.array_equal(_host(r1[tidx]), e1), spec
+        assert torch.equal(hb.hb_open(r0, r1), x * dexp), spec       # every element
+        del r0, r1
+    if "drelu" in modes:
+        q0, q1, _ = hb.hb_drelu(s0, s1, k, m, seed)
+        e0, e1 = oracle.evaluate_at(h0, h1, idx.astype(np.uint64), k, m, seed, oracle.WHAT_DRELU)
+        assert np.array_equal(_host(q0[tidx]), e0) and np.array_equal(_host(q1[tidx]), e1), spec
+        assert torch.equal(hb.hb_open(q0, q1), dexp), spec
+    return n
+
+
+def test_resnet18_cifar_batch512_full_size():
+    """The headline workload in the configuration the benchmark times: one launch per tensor, per-tensor seeds."""
+    rng = np.random.default_rng(3)
+    total = 0
+    for spec in workloads.resnet18_cifar_batch512():
+        total += _check_large(spec, hb.hb_tensor_seed(SEED, spec.tensor_id), rng)
+        torch.cuda.empty_cache()
+    assert total == 285212672
+
+
+def test_width_sweep_full_size():
+    rng = np.random.default_rng(4)
+    for spec in workloads.width_sweep():
+        _check_large(spec, SEED + spec.w, rng, modes=("relu", "drelu"))
+        torch.cuda.empty_cache()
+
+
+def test_resnet18_imagenet_batch64_full_size():
+    rng = np.random.default_rng(5)
+    total = 0
+    for spec in workloads.resnet18_imagenet():
+        total += _check_large(spec, hb.hb_tensor_seed(SEED, spec.tensor_id), rng)
+        torch.cuda.empty_cache()
+    assert total == 147718144
+
+
+# ----------------------------------------------------------------------------------------------
+# boundary behaviour
+# ----------------------------------------------------------------------------------------------
+
+def test_in_place_unaligned_and_streams():
+    rng = np.random.default_rng(77)
+    n = 5003
+    s0, s1 = _rand_shares(rng, n + 1)
+    for (k, m) in [(12, 20), (0, 64), (8, 14)]:
+        e0, e1, _ = oracle.relu(s0[1:], s1[1:], k, m, SEED)
+        # buffers that are only 8-byte aligned
+        d0, d1 = _dev(s0)[1:], _dev(s1)[1:]
+        assert d0.data_ptr() % 16 == 8
+        o0 = torch.empty(n + 1, dtype=torch.int64, device=DEV)[1:]
+        o1 = torch.empty(n + 1, dtype=torch.int64, device=DEV)[1:]
+        hb.hb_relu(d0, d1, k, m, SEED, o0, o1)
+        assert np.array_equal(_host(o0), e0) and np.array_equal(_host(o1), e1)
+        # in place, on a side stream
+        st = torch.cuda.Stream()
+        st.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(st):
+            hb.hb_relu(d0, d1, k, m, SEED, d0, d1)
+        st.synchronize()
+        assert np.array_equal(_host(d0), e0) and np.array_equal(_host(d1), e1)
+        # mixed: aligned inputs, unaligned outputs
+        a0, a1 = _dev(s0[1:].copy()), _dev(s1[1:].copy())
+        hb.hb_relu(a0, a1, k, m, SEED, o0, o1)
+        assert np.array_equal(_host(o0), e0) and np.array_equal(_host(o1), e1)
+
+
+def test_open_matches_oracle():
+    rng = np.random.default_rng(78)
+    for n in (1, 2, 3, 1000, 65537):
+        a, b = _rand_shares(rng, n)
+        for binary in (False, True):
+            got = _host(hb.hb_open(_dev(a), _dev(b), binary))
+            assert np.array_equal(got, oracle.open_shares(a, b, binary))
+    a, b = _rand_shares(rng, 1002)
+    da, db = _dev(a)[1:], _dev(b)[1:]
+    hb.hb_open(da, db, False, out=da)
+    assert np.array_equal(_host(da), oracle.open_shares(a[1:], b[1:]))
+
+
+def test_repeatable_and_seed_sensitive():
+    rng = np.random.default_rng(79)
+    s0, s1 = _rand_shares(rng, 4099)
+    d0, d1 = _dev(s0), _dev(s1)
+    a0, a1, _ = hb.hb_relu(d0, d1, 12, 20, SEED)
+    b0, b1, _ = hb.hb_relu(d0, d1, 12, 20, SEED)
+    c0, c1, _ = hb.hb_relu(d0, d1, 12, 20, SEED + 1)
+    assert torch.equal(a0, b0) and torch.equal(a1, b1)
+    assert (a0 != c0).float().mean().item() > 0.99
+    assert torch.equal(a0 + a1, c0 + c1)
+
+
+def test_errors_are_reported_not_launched():
+    n = 1024
+    t = [torch.zeros(n, dtype=torch.int64, device=DEV) for _ in range(4)]
+    p = [x.data_ptr() for x in t]
+    bits = ctypes.c_uint64(123)
+    call = lambda name, *a: hb.raw(name, *a)
+    ok = (p[0], p[1], n, 12, 20, SEED, p[2], p[3], ctypes.byref(bits), None)
+    assert call("hb_relu", *ok) == hb.HB_OK and bits.value == n * 241
+    for (k, m) in [(-1, 8), (8, 8), (9, 8), (0, 65), (60, 70)]:
+        for name in ("hb_relu", "hb_drelu", "hb_sign_shares"):
+            assert call(name, p[0], p[1], n, k, m, SEED, p[2], p[3], None, None) == hb.HB_EINVAL
+    for bad in range(4):
+        q = list(p)
+        q[bad] = None
+        assert call("hb_relu", q[0], q[1], n, 12, 20, SEED, q[2], q[3], None, None) == hb.HB_EINVAL
+        q = list(p)
+        q[bad] = p[bad] + 4
+        assert call("hb_relu", q[0], q[1], n, 12, 20, SEED, q[2], q[3], None, None) == hb.HB_EALIGN
+    # null pointers are fine when there is nothing to do
+    assert call("hb_relu", None, None, 0, 12, 20, SEED, None, None, ctypes.byref(bits), None) == hb.HB_OK
+    assert bits.value == 0
+    assert call("hb_relu", None, None, 0, 20, 12, SEED, None, None, None, None) == hb.HB_EINVAL
+    # partial overlap and output/output overlap
+    assert call("hb_relu", p[0], p[1], n - 8, 12, 20, SEED, p[0] + 64, p[3], None, None) == hb.HB_EINVAL
+    assert call("hb_relu", p[0], p[1], n, 12, 20, SEED, p[2], p[2], None, None) == hb.HB_EINVAL
+    assert call("hb_open", p[0], p[1], n, 0, None, None) == hb.HB_EINVAL
+    assert call("hb_open", p[0], p[1] + 4, n, 0, p[2], None) == hb.HB_EALIGN
+    assert call("hb_relu", p[0], p[1], (1 << 40) + 1, 12, 20, SEED, p[2], p[3], None, None) == hb.HB_EINVAL
+    torch.cuda.synchronize()
+    # nothing above wrote to the outputs after the first, valid call
+    assert call("hb_relu", *ok) == hb.HB_OK
+    torch.cuda.synchronize()
