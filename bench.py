@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the secret-shared ReLU hot path on one MI355X.
+
+A step is one pass of hb_relu over the headline workload: the 17 ReLU input tensors of ResNet18 on
+3x32x32 images at batch 512 (285,212,672 elements, 2^16 fixed point, int64 shares), slice
+(k, m) = (12, 20), one launch per tensor with its own seed.  Inputs and outputs are resident in HBM
+before the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+ROOT_SEED = 0x2309048750000001
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+BYTES_PER_ELEMENT = 32         # two int64 shares read, two written
+
+
+def _time_launches(fn, reps, torch):
+    """Average duration in ms of `fn` (one launch) over `reps` launches, by events on the current stream."""
+    fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (both parties are simulated on it; there is no "
+                 "sharded or multi-rank path) -- run with --gpus 1")
+
+    import torch
+    from paper_2309_04875_amd import hb, workloads
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    hb.load()   # fails loudly when the HIP library has not been built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    # ---- inputs resident in HBM ------------------------------------------------------------
+    specs = workloads.resnet18_cifar_batch512()
+    tensors = []
+    for spec in specs:
+        _, s0, s1 = workloads.materialize_on_device(spec, dev)
+        tensors.append((spec, s0, s1, torch.empty_like(s0), torch.empty_like(s1),
+                        hb.hb_tensor_seed(ROOT_SEED, spec.tensor_id)))
+    n_total = sum(s.n for s in specs)
+    k, m = specs[0].k, specs[0].m
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        bits = 0
+        for (spec, s0, s1, o0, o1, seed) in tensors:
+            if events is not None:
+                a = torch.cuda.Event(enable_timing=True)
+                b = torch.cuda.Event(enable_timing=True)
+                a.record()
+            bits += hb.hb_relu(s0, s1, spec.k, spec.m, seed, o0, o1)[2]
+            if events is not None:
+                b.record()
+                events.append((a, b))
+        return bits
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, per-launch HIP events on the launch stream ----------
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        opened = step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = n_total / (ms_per_step * 1e-3)
+
+    launch_ms = [a.elapsed_time(b) for (a, b) in events]
+    kernel_ms_per_step = sum(launch_ms) / args.steps
+    launches = len(launch_ms)
+    avg_launch_ms = sum(launch_ms) / launches
+    bytes_per_launch = BYTES_PER_ELEMENT * n_total / len(tensors)      # average over the 17 launches of a step
+    achieved_gbs = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
+
+    # ---- side figures, outside the timed region ---------------------------------------------
+    spec0, s0, s1, o0, o1, seed0 = tensors[0]
+    extra = {}
+    ms = _time_launches(lambda: hb.hb_relu(s0, s1, 0, 64, seed0, o0, o1), 5, torch)
+    extra["relu_w64_elems_per_s"] = spec0.n / (ms * 1e-3)
+    extra["relu_w64_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    ms = _time_launches(lambda: hb.hb_relu(s0, s1, k, m, seed0, o0, o1), 10, torch)
+    extra["relu_w8_elems_per_s_largest_tensor"] = spec0.n / (ms * 1e-3)
+    ms = _time_launches(lambda: hb.hb_drelu(s0, s1, k, m, seed0, o0, o1), 10, torch)
+    extra["drelu_w8_elems_per_s"] = spec0.n / (ms * 1e-3)
+    ms = _time_launches(lambda: hb.hb_open(s0, s1, False, out=o0), 10, torch)
+    extra["open_copy_ceiling_gbs"] = 24 * spec0.n / (ms * 1e-3) / 1e9
+    extra["opened_bits_per_element"] = opened / n_total
+    extra["opened_bits_vs_64bit_baseline"] = hb.BASELINE_BITS_PER_ELEMENT / (opened / n_total)
+
+    # ---- CPU baseline: the oracle as it stands on this machine's host cores, bounded sample ------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        sample = tensors[:2]                     # tensors 0 and 1 of the workload: 2 x 2^25 elements
+        host = [(sp, a.cpu().numpy(), b.cpu().numpy(), sd) for (sp, a, b, _, _, sd) in sample]
+        c0 = time.perf_counter()
+        for (sp, a, b, sd) in host:
+            oracle.evaluate(a, b, sp.k, sp.m, sd, oracle.WHAT_RELU, threads=cores)
+        c1 = time.perf_counter()
+        n_cpu = sum(sp.n for (sp, _, _, _) in host)
+        cpu = {"value": n_cpu / (c1 - c0), "unit": "elements/s", "cores": cores, "kind": "oracle",
+               "sample": "tensors 0-1 of the workload in full (%d elements), hb_relu at (12,20), "
+                         "element range split over %d threads" % (n_cpu, cores)}
+
+    out = {
+        "metric": "secret-shared ReLU elems/s at w=8 and w=64; % of HBM roofline",
+        "value": value,
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {"workload": "resnet18_cifar32_relu_set_batch512_k12_m20 (17 tensors, 285,212,672 elements, w=8)",
+                   "elements": n_total, "k": k, "m": m, "launches_per_step": len(tensors),
+                   "root_seed": ROOT_SEED},
+        "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "hb::group_kernel<8, relu, vec16>",
+                     "avg_launch_ms": avg_launch_ms, "kernel_ms_per_step": kernel_ms_per_step,
+                     "algorithmic_bytes_per_element": BYTES_PER_ELEMENT},
+        "cpu_baseline": cpu,
+        "extra": extra,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
