@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <utility>
 
@@ -131,6 +132,15 @@ LauncherTable &launcher_table()
 {
     static LauncherTable table = {};
     return table;
+}
+
+bool force_group_kernel()
+{
+    static const bool forced = [] {
+        const char *v = std::getenv("HB_KERNEL");
+        return v != nullptr && std::strcmp(v, "group") == 0;
+    }();
+    return forced;
 }
 }  // namespace hb
 

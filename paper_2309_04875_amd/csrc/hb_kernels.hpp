@@ -6,6 +6,8 @@
 // memory and nothing but the output shares is written: the algorithmic traffic is 32 bytes per element.
 #pragma once
 
+#include <type_traits>
+
 #include "hb_protocol.hpp"
 
 namespace hb {
@@ -128,6 +130,141 @@ open_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int binary, uint
         }
     } else {
         if (t < n) out[t] = binary ? (x0[t] ^ x1[t]) : (x0[t] + x1[t]);
+    }
+}
+
+
+// ------------------------------------------------------------------------------------------------
+// Tile kernel (slice widths with 2 <= L <= 16, 16-byte aligned buffers).
+//
+// A wavefront owns a tile of 64*L consecutive elements = 64 groups.  Memory traffic and the
+// per-element arithmetic are laid out for coalescing: lane l loads / finishes / stores the element
+// pairs (2(c*64 + l), +1), so every load and store instruction of the wave covers 1 KiB of
+// consecutive addresses.  The circuit is laid out for dealer-word sharing: lane l evaluates group l
+// of the tile.  The two layouts meet in the wave's private piece of LDS: owners deposit the sliced
+// shares of their elements, group lanes collect the L fields of their group, and after the circuit
+// each group lane leaves its sign shares and B2A dealer word for the owners of its elements.
+// All exchange stays inside one wavefront, whose LDS operations execute in program order, so no
+// workgroup barrier is needed; wave_sync() only keeps the compiler from moving LDS accesses across.
+// ------------------------------------------------------------------------------------------------
+
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int W>
+struct TileTraits {
+    using S = Shape<W>;
+    static constexpr int L = S::L;
+    static constexpr bool kSupported = (L >= 2 && L <= 16);
+    static constexpr int kTile = kWave * L;                     // elements per wavefront
+    static constexpr int kPairs = (L + 1) / 2;                  // element pairs per lane (last may be idle when L is odd)
+    static constexpr int kHalf = (W <= 16) ? 16 : 32;           // bits per party inside an LDS entry
+    using Entry = typename std::conditional<(W <= 16), uint32_t, uint64_t>::type;
+};
+
+template <int W, int MODE>
+__global__ void __launch_bounds__(kBlock)
+tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t *o0,
+            uint64_t *o1)
+{
+    using T = TileTraits<W>;
+    using S = Shape<W>;
+    using Entry = typename T::Entry;
+    constexpr int L = T::L;
+    static_assert(T::kSupported, "tile kernel needs 2 <= L <= 16");
+
+    __shared__ Entry slices_all[kWavesPerBlock][T::kTile];   // per element: party 0 slice | party 1 slice << kHalf
+    __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];     // per group: {sign shares, B2A dealer word}
+
+    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
+    const uint64_t tile0 = tile * T::kTile;
+    if (tile0 >= n) return;                  // whole wavefront beyond the tensor (uniform per wave)
+    Entry *slices = slices_all[wv];
+    U64x2 *verdict = verdict_all[wv];
+
+    // ---- owners: load, slice, deposit -------------------------------------------------------
+    U64x2 xa[T::kPairs], xb[T::kPairs];
+#pragma unroll
+    for (int c = 0; c < T::kPairs; ++c) {
+        const int e = 2 * (c * kWave + lane);
+        xa[c] = U64x2{0, 0};
+        xb[c] = U64x2{0, 0};
+        if (e < T::kTile) {
+            const uint64_t i = tile0 + e;
+            if (i + 1 < n) {
+                xa[c] = *reinterpret_cast<const U64x2 *>(x0 + i);
+                xb[c] = *reinterpret_cast<const U64x2 *>(x1 + i);
+            } else if (i < n) {
+                xa[c].a = x0[i];
+                xb[c].a = x1[i];
+            }
+            const Entry e0 = (Entry)((xa[c].a >> k) & S::kField) | ((Entry)((xb[c].a >> k) & S::kField) << T::kHalf);
+            const Entry e1 = (Entry)((xa[c].b >> k) & S::kField) | ((Entry)((xb[c].b >> k) & S::kField) << T::kHalf);
+            slices[e] = e0;
+            slices[e + 1] = e1;
+        }
+    }
+    wave_sync();
+
+    // ---- group lanes: collect fields, run the circuit, publish the verdict ----------------------
+    uint64_t u0 = 0, u1 = 0;
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        const Entry en = slices[lane * L + j];
+        u0 |= (uint64_t)(en & (Entry)S::kField) << (j * W);
+        u1 |= (uint64_t)(en >> T::kHalf) << (j * W);
+    }
+    const uint64_t g = tile * kWave + lane;
+    const uint64_t zg = seedB + (g * (uint64_t)S::kWordsPerGroup + 1) * kGamma;
+    const Pair sum = a2b_sum<W>(u0, u1, zg);
+    {
+        // sign of field j: party 0 at bit jW, party 1 at bit jW + 1
+        const uint64_t ones = S::ones();
+        const uint64_t sg = ((sum.p0 >> (W - 1)) & ones) | (((sum.p1 >> (W - 1)) & ones) << 1);
+        uint64_t wb = 0;
+        if (MODE != kSign) wb = mix64(zg + (uint64_t)(5 * S::kGates) * kGamma);
+        verdict[lane] = U64x2{sg, wb};
+    }
+    wave_sync();
+
+    // ---- owners: pick up the verdict of each element's group, finish, store ---------------------
+#pragma unroll
+    for (int c = 0; c < T::kPairs; ++c) {
+        const int e = 2 * (c * kWave + lane);
+        if (e < T::kTile) {
+            const uint64_t i = tile0 + e;
+            Pair r[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int eh = e + h;
+                const int grp = eh / L, j = eh - grp * L;
+                const U64x2 v = verdict[grp];
+                const Pair sign{(v.a >> (j * W)) & 1, (v.a >> (j * W + 1)) & 1};
+                if (MODE == kSign) {
+                    r[h] = sign;
+                } else {
+                    const Pair rho{(v.b >> (2 * j)) & 1, (v.b >> (2 * j + 1)) & 1};
+                    const uint64_t zA = seedA + (6 * (i + h) + 1) * kGamma;
+                    const Pair D = b2a_drelu(sign, rho, zA);
+                    r[h] = (MODE == kDrelu) ? D : beaver_mul(Pair{h ? xa[c].b : xa[c].a, h ? xb[c].b : xb[c].a}, D, zA);
+                }
+            }
+            if (i + 1 < n) {
+                *reinterpret_cast<U64x2 *>(o0 + i) = U64x2{r[0].p0, r[1].p0};
+                *reinterpret_cast<U64x2 *>(o1 + i) = U64x2{r[0].p1, r[1].p1};
+            } else if (i < n) {
+                o0[i] = r[0].p0;
+                o1[i] = r[0].p1;
+            }
+        }
     }
 }
 

@@ -17,4 +17,7 @@ struct LauncherTable {
 
 LauncherTable &launcher_table();
 
+// Debug knob: HB_KERNEL=group in the environment (read once) sends every width to the thread-per-group kernel.
+bool force_group_kernel();
+
 }  // namespace hb
