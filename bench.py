@@ -3,8 +3,9 @@
 
 A step is one pass of hb_relu over the headline workload: the 17 ReLU input tensors of ResNet18 on
 3x32x32 images at batch 512 (285,212,672 elements, 2^16 fixed point, int64 shares), slice
-(k, m) = (12, 20), one launch per tensor with its own seed.  Inputs and outputs are resident in HBM
-before the timed region starts.  Prints ONE JSON line.
+(k, m) = (12, 20), every tensor with its own seed, issued through hb_relu_batch (one kernel launch for
+the 17 tensors).  Inputs and outputs are resident in HBM before the timed region starts.  The GPU's clocks
+ramp up over the first tens of milliseconds of load, so the default warm-up is 50 steps.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
 """
@@ -25,7 +26,8 @@ BYTES_PER_ELEMENT = 32         # two int64 shares read, two written
 
 def _time_launches(fn, reps, torch):
     """Average duration in ms of `fn` (one launch) over `reps` launches, by events on the current stream."""
-    fn()
+    for _ in range(max(1, reps // 2)):      # same load beforehand, so the clocks have settled
+        fn()
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
@@ -40,9 +42,10 @@ def _time_launches(fn, reps, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the side measurements (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (both parties are simulated on it; there is no "
@@ -68,54 +71,51 @@ def main():
     k, m = specs[0].k, specs[0].m
     torch.cuda.synchronize()
 
-    def step(events=None):
-        bits = 0
-        for (spec, s0, s1, o0, o1, seed) in tensors:
-            if events is not None:
-                a = torch.cuda.Event(enable_timing=True)
-                b = torch.cuda.Event(enable_timing=True)
-                a.record()
-            bits += hb.hb_relu(s0, s1, spec.k, spec.m, seed, o0, o1)[2]
-            if events is not None:
-                b.record()
-                events.append((a, b))
-        return bits
+    batch = hb.make_batch([(s0, s1, o0, o1, spec.k, spec.m, seed) for (spec, s0, s1, o0, o1, seed) in tensors])
+
+    def step():
+        return hb.hb_relu_batch(batch)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps, per-launch HIP events on the launch stream ----------
-    events = []
+    # ---- timed region: exactly K steps; a HIP event pair on the launch stream brackets each step's launch ----
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        opened = step(events)
+    for (a, b) in events:
+        a.record()
+        opened = step()
+        b.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = n_total / (ms_per_step * 1e-3)
 
-    launch_ms = [a.elapsed_time(b) for (a, b) in events]
-    kernel_ms_per_step = sum(launch_ms) / args.steps
-    launches = len(launch_ms)
-    avg_launch_ms = sum(launch_ms) / launches
-    bytes_per_launch = BYTES_PER_ELEMENT * n_total / len(tensors)      # average over the 17 launches of a step
+    launch_ms = [a.elapsed_time(b) for (a, b) in events]      # one launch of hb::tile_batch_kernel<8, relu> per step
+    avg_launch_ms = sum(launch_ms) / len(launch_ms)
+    kernel_ms_per_step = avg_launch_ms
+    bytes_per_launch = BYTES_PER_ELEMENT * n_total
     achieved_gbs = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
 
     # ---- side figures, outside the timed region ---------------------------------------------
     spec0, s0, s1, o0, o1, seed0 = tensors[0]
-    extra = {}
-    ms = _time_launches(lambda: hb.hb_relu(s0, s1, 0, 64, seed0, o0, o1), 5, torch)
-    extra["relu_w64_elems_per_s"] = spec0.n / (ms * 1e-3)
-    extra["relu_w64_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
-    ms = _time_launches(lambda: hb.hb_relu(s0, s1, k, m, seed0, o0, o1), 10, torch)
-    extra["relu_w8_elems_per_s_largest_tensor"] = spec0.n / (ms * 1e-3)
-    ms = _time_launches(lambda: hb.hb_drelu(s0, s1, k, m, seed0, o0, o1), 10, torch)
-    extra["drelu_w8_elems_per_s"] = spec0.n / (ms * 1e-3)
-    ms = _time_launches(lambda: hb.hb_open(s0, s1, False, out=o0), 10, torch)
-    extra["open_copy_ceiling_gbs"] = 24 * spec0.n / (ms * 1e-3) / 1e9
-    extra["opened_bits_per_element"] = opened / n_total
-    extra["opened_bits_vs_64bit_baseline"] = hb.BASELINE_BITS_PER_ELEMENT / (opened / n_total)
+    extra = {"opened_bits_per_element": opened / n_total,
+             "opened_bits_vs_64bit_baseline": hb.BASELINE_BITS_PER_ELEMENT / (opened / n_total)}
+    if not args.no_extra:
+        def per_tensor_step():
+            for (spec, a, b, c, d, seed) in tensors:
+                hb.hb_relu(a, b, spec.k, spec.m, seed, c, d)
+        ms = _time_launches(per_tensor_step, 40, torch)
+        extra["relu_w8_elems_per_s_one_launch_per_tensor"] = n_total / (ms * 1e-3)
+        ms = _time_launches(lambda: hb.hb_relu(s0, s1, 0, 64, seed0, o0, o1), 60, torch)
+        extra["relu_w64_elems_per_s"] = spec0.n / (ms * 1e-3)
+        extra["relu_w64_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+        ms = _time_launches(lambda: hb.hb_drelu(s0, s1, k, m, seed0, o0, o1), 300, torch)
+        extra["drelu_w8_elems_per_s"] = spec0.n / (ms * 1e-3)
+        extra["drelu_w8_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+        ms = _time_launches(lambda: hb.hb_open(s0, s1, False, out=o0), 300, torch)
+        extra["open_copy_ceiling_gbs"] = 24 * spec0.n / (ms * 1e-3) / 1e9
 
     # ---- CPU baseline: the oracle as it stands on this machine's host cores, bounded sample ------
     cpu = None
@@ -147,11 +147,11 @@ def main():
         "dtype": "u64",
         "data": "synthetic",
         "config": {"workload": "resnet18_cifar32_relu_set_batch512_k12_m20 (17 tensors, 285,212,672 elements, w=8)",
-                   "elements": n_total, "k": k, "m": m, "launches_per_step": len(tensors),
+                   "elements": n_total, "k": k, "m": m, "launches_per_step": 1, "tensors_per_step": len(tensors),
                    "root_seed": ROOT_SEED},
         "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "hb::group_kernel<8, relu, vec16>",
+                     "kernel": "hb::tile_batch_kernel<8, relu>",
                      "avg_launch_ms": avg_launch_ms, "kernel_ms_per_step": kernel_ms_per_step,
                      "algorithmic_bytes_per_element": BYTES_PER_ELEMENT},
         "cpu_baseline": cpu,

@@ -82,6 +82,29 @@ HB_API int hb_sign_shares(const int64_t *share0, const int64_t *share1, size_t n
  */
 HB_API int hb_open(const int64_t *share0, const int64_t *share1, size_t n, int binary, int64_t *out, void *stream);
 
+/*
+ * One tensor of a batched call: the arguments of hb_relu / hb_drelu for that tensor.
+ */
+typedef struct hb_tensor {
+    const int64_t *share0, *share1; /* device, n elements each */
+    int64_t *out0, *out1;           /* device, n elements each */
+    size_t n;
+    int k, m;
+    uint64_t seed;                  /* e.g. hb_tensor_seed(root, tensor index) */
+} hb_tensor;
+
+/*
+ * A set of ReLU layers' tensors in as few launches as possible (the per-layer (k, m) of Sec. 4.2 are
+ * fixed offline, so a whole set can be issued at once; one launch per distinct slice width when the
+ * buffers are 16-byte aligned).  `tensors` is a HOST array of `count` descriptors, read before the
+ * call returns.  The result for every tensor is bit-for-bit what hb_relu (hb_drelu) gives for that
+ * tensor alone.  All descriptors are validated before anything is enqueued; besides the per-tensor
+ * rules, no output of one tensor may overlap any buffer of another.  opened_bits receives the sum
+ * over the tensors.
+ */
+HB_API int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream);
+HB_API int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream);
+
 /* Seed of tensor `tensor_id` in a set of tensors keyed by one root seed (host-only, no GPU work). */
 HB_API uint64_t hb_tensor_seed(uint64_t root_seed, uint64_t tensor_id);
 

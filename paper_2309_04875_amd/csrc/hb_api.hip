@@ -92,14 +92,14 @@ bool all_aligned16(const void *const *ptrs, int count)
     return true;
 }
 
-int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
-        int64_t *out1, uint64_t *opened_bits, void *stream)
+// Argument rules of one tensor of a call (no launch): slice, pointers, alignment, device memory, overlaps.
+int validate_tensor(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, const int64_t *out0,
+                    const int64_t *out1)
 {
     if (!valid_slice(k, m)) return HB_EINVAL;
     const void *ptrs[4] = {share0, share1, out0, out1};
     const int st = check_common(ptrs, 4, n);
     if (st != HB_OK) return st;
-    const int w = m - k;
     if (n > 0) {
         const Range i0 = range_of(share0, n), i1 = range_of(share1, n), r0 = range_of(out0, n), r1 = range_of(out1, n);
         // an output may coincide with an input; every other overlap is refused
@@ -107,6 +107,16 @@ int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k,
         if (!(same(r0, i0) || disjoint(r0, i0)) || !(same(r0, i1) || disjoint(r0, i1))) return HB_EINVAL;
         if (!(same(r1, i0) || disjoint(r1, i0)) || !(same(r1, i1) || disjoint(r1, i1))) return HB_EINVAL;
     }
+    return HB_OK;
+}
+
+int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
+        int64_t *out1, uint64_t *opened_bits, void *stream)
+{
+    const int st = validate_tensor(share0, share1, n, k, m, out0, out1);
+    if (st != HB_OK) return st;
+    const void *ptrs[4] = {share0, share1, out0, out1};
+    const int w = m - k;
     uint64_t bits = 0;
     if (mode == hb::kSign) {
         bits = (uint64_t)n * (2ull * (uint64_t)w * (1 + 2 * (uint64_t)rounds_of(w)));
@@ -120,6 +130,93 @@ int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k,
         const hipError_t e = f((const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, k, seedB, seedA,
                                (uint64_t *)out0, (uint64_t *)out1, all_aligned16(ptrs, 4), (hipStream_t)stream);
         if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    }
+    if (opened_bits) *opened_bits = bits;
+    return HB_OK;
+}
+
+int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
+{
+    if (count > 0 && tensors == nullptr) return HB_EINVAL;
+    if (count > 4096) return HB_EINVAL;
+    // validate everything first: on error nothing is enqueued
+    for (size_t i = 0; i < count; ++i) {
+        const hb_tensor &t = tensors[i];
+        const int st = validate_tensor(t.share0, t.share1, t.n, t.k, t.m, t.out0, t.out1);
+        if (st != HB_OK) return st;
+    }
+    for (size_t i = 0; i < count; ++i) {
+        const hb_tensor &a = tensors[i];
+        if (a.n == 0) continue;
+        const Range outs[2] = {range_of(a.out0, a.n), range_of(a.out1, a.n)};
+        for (size_t j = 0; j < count; ++j) {
+            const hb_tensor &b = tensors[j];
+            if (j == i || b.n == 0) continue;
+            const Range others[4] = {range_of(b.share0, b.n), range_of(b.share1, b.n), range_of(b.out0, b.n),
+                                     range_of(b.out1, b.n)};
+            for (const Range &o : outs) {
+                for (const Range &r : others) {
+                    if (!disjoint(o, r)) return HB_EINVAL;
+                }
+            }
+        }
+    }
+    uint64_t bits = 0;
+    bool taken[4096] = {};
+    for (size_t i = 0; i < count; ++i) {
+        if (taken[i]) continue;
+        const hb_tensor &first = tensors[i];
+        const int w = first.m - first.k;
+        taken[i] = true;
+        bits += hb_opened_bits(mode == hb::kRelu, first.k, first.m, first.n);
+        if (first.n == 0) continue;
+        const hb::BatchLauncher bl = hb::launcher_table().batch[mode][w - 1];
+        const void *p0[4] = {first.share0, first.share1, first.out0, first.out1};
+        if (bl == nullptr || hb::force_group_kernel() || !all_aligned16(p0, 4)) {
+            const int st = run(mode, first.share0, first.share1, first.n, first.k, first.m, first.seed, first.out0,
+                               first.out1, nullptr, stream);
+            if (st != HB_OK) return st;
+            continue;
+        }
+        // gather the later tensors of the same width that can share the launch
+        hb::BatchArgs args = {};
+        auto add = [&](const hb_tensor &t) {
+            const uint64_t L = 64 / (uint64_t)w;    // tile-kernel widths have L = floor(64 / w) <= 16
+            const uint64_t tiles = (t.n + hb::kWave * L - 1) / (hb::kWave * L);
+            hb::BatchTensor &d = args.t[args.count];
+            d.x0 = (const uint64_t *)t.share0;
+            d.x1 = (const uint64_t *)t.share1;
+            d.o0 = (uint64_t *)t.out0;
+            d.o1 = (uint64_t *)t.out1;
+            d.n = t.n;
+            d.seedB = hb::stream_word(t.seed, 0);
+            d.seedA = hb::stream_word(t.seed, 1);
+            d.k = t.k;
+            args.tile_end[args.count] = (args.count ? args.tile_end[args.count - 1] : 0) + tiles;
+            ++args.count;
+        };
+        add(first);
+        auto flush = [&]() -> int {
+            if (args.count == 0) return HB_OK;
+            const hipError_t e = bl(args, (hipStream_t)stream);
+            args = hb::BatchArgs{};
+            return e == hipSuccess ? HB_OK : fail_hip(e, "kernel launch");
+        };
+        for (size_t j = i + 1; j < count; ++j) {
+            const hb_tensor &t = tensors[j];
+            if (taken[j] || t.m - t.k != w || t.n == 0) continue;
+            const void *pj[4] = {t.share0, t.share1, t.out0, t.out1};
+            if (!all_aligned16(pj, 4)) continue;
+            if (args.count == hb::kBatchMax) {
+                const int st = flush();
+                if (st != HB_OK) return st;
+            }
+            taken[j] = true;
+            bits += hb_opened_bits(mode == hb::kRelu, t.k, t.m, t.n);
+            add(t);
+        }
+        const int st = flush();
+        if (st != HB_OK) return st;
     }
     if (opened_bits) *opened_bits = bits;
     return HB_OK;
@@ -162,6 +259,16 @@ int hb_sign_shares(const int64_t *share0, const int64_t *share1, size_t n, int k
                    int64_t *out1, uint64_t *opened_bits, void *stream)
 {
     return run(hb::kSign, share0, share1, n, k, m, seed, out0, out1, opened_bits, stream);
+}
+
+int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
+{
+    return run_batch(hb::kRelu, tensors, count, opened_bits, stream);
+}
+
+int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
+{
+    return run_batch(hb::kDrelu, tensors, count, opened_bits, stream);
 }
 
 int hb_open(const int64_t *share0, const int64_t *share1, size_t n, int binary, int64_t *out, void *stream)

@@ -165,36 +165,36 @@ struct TileTraits {
     static constexpr bool kSupported = (L >= 2 && L <= 16);
     static constexpr int kTile = kWave * L;                     // elements per wavefront
     static constexpr int kPairs = (L + 1) / 2;                  // element pairs per lane (last may be idle when L is odd)
-    static constexpr int kHalf = (W <= 16) ? 16 : 32;           // bits per party inside an LDS entry
+    // W in {4, 8, 16, 32}: a pair of fields is an addressable LDS item (1, 2, 4, 8 bytes), so owners can
+    // write their pair straight into the group's packed word.  Other widths go through one entry per element.
+    static constexpr bool kPacked = (W == 4 || W == 8 || W == 16 || W == 32);
+    using Item = typename std::conditional<(W == 4), uint8_t,
+                 typename std::conditional<(W == 8), uint16_t,
+                 typename std::conditional<(W == 16), uint32_t, uint64_t>::type>::type>::type;
+    static constexpr int kHalf = (W <= 16) ? 16 : 32;           // bits per party inside an unpacked LDS entry
     using Entry = typename std::conditional<(W <= 16), uint32_t, uint64_t>::type;
+    // LDS bytes per wavefront for the slices
+    static constexpr int kSliceBytes = kPacked ? 2 * kWave * 8 : kTile * (int)sizeof(Entry);
 };
 
+// Work of one wavefront on wave-tile `tile` of one tensor.  slice_lds / verdict: this wave's LDS.
 template <int W, int MODE>
-__global__ void __launch_bounds__(kBlock)
-tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t *o0,
-            uint64_t *o1)
+__device__ __forceinline__ void tile_body(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t seedB,
+                                          uint64_t seedA, uint64_t *o0, uint64_t *o1, uint64_t tile, int lane,
+                                          unsigned char *slice_lds, U64x2 *verdict)
 {
     using T = TileTraits<W>;
     using S = Shape<W>;
-    using Entry = typename T::Entry;
     constexpr int L = T::L;
     static_assert(T::kSupported, "tile kernel needs 2 <= L <= 16");
-
-    __shared__ Entry slices_all[kWavesPerBlock][T::kTile];   // per element: party 0 slice | party 1 slice << kHalf
-    __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];     // per group: {sign shares, B2A dealer word}
-
-    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-    const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     const uint64_t tile0 = tile * T::kTile;
-    if (tile0 >= n) return;                  // whole wavefront beyond the tensor (uniform per wave)
-    Entry *slices = slices_all[wv];
-    U64x2 *verdict = verdict_all[wv];
 
     // ---- owners: load, slice, deposit -------------------------------------------------------
     U64x2 xa[T::kPairs], xb[T::kPairs];
 #pragma unroll
     for (int c = 0; c < T::kPairs; ++c) {
-        const int e = 2 * (c * kWave + lane);
+        const int pr = c * kWave + lane;     // pair index inside the tile
+        const int e = 2 * pr;
         xa[c] = U64x2{0, 0};
         xb[c] = U64x2{0, 0};
         if (e < T::kTile) {
@@ -206,21 +206,37 @@ tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t 
                 xa[c].a = x0[i];
                 xb[c].a = x1[i];
             }
-            const Entry e0 = (Entry)((xa[c].a >> k) & S::kField) | ((Entry)((xb[c].a >> k) & S::kField) << T::kHalf);
-            const Entry e1 = (Entry)((xa[c].b >> k) & S::kField) | ((Entry)((xb[c].b >> k) & S::kField) << T::kHalf);
-            slices[e] = e0;
-            slices[e + 1] = e1;
+            if constexpr (T::kPacked) {
+                // the pair's two fields of party 0 / party 1, already at their place relative to the pair
+                using Item = typename T::Item;
+                Item *w0 = reinterpret_cast<Item *>(slice_lds);
+                Item *w1 = reinterpret_cast<Item *>(slice_lds + kWave * 8);
+                w0[pr] = (Item)(((xa[c].a >> k) & S::kField) | (((xa[c].b >> k) & S::kField) << (W % 64)));
+                w1[pr] = (Item)(((xb[c].a >> k) & S::kField) | (((xb[c].b >> k) & S::kField) << (W % 64)));
+            } else {
+                using Entry = typename T::Entry;
+                Entry *slices = reinterpret_cast<Entry *>(slice_lds);
+                slices[e] = (Entry)((xa[c].a >> k) & S::kField) | ((Entry)((xb[c].a >> k) & S::kField) << T::kHalf);
+                slices[e + 1] = (Entry)((xa[c].b >> k) & S::kField) | ((Entry)((xb[c].b >> k) & S::kField) << T::kHalf);
+            }
         }
     }
     wave_sync();
 
     // ---- group lanes: collect fields, run the circuit, publish the verdict ----------------------
     uint64_t u0 = 0, u1 = 0;
+    if constexpr (T::kPacked) {
+        u0 = reinterpret_cast<const uint64_t *>(slice_lds)[lane];
+        u1 = reinterpret_cast<const uint64_t *>(slice_lds + kWave * 8)[lane];
+    } else {
+        using Entry = typename T::Entry;
+        const Entry *slices = reinterpret_cast<const Entry *>(slice_lds);
 #pragma unroll
-    for (int j = 0; j < L; ++j) {
-        const Entry en = slices[lane * L + j];
-        u0 |= (uint64_t)(en & (Entry)S::kField) << (j * W);
-        u1 |= (uint64_t)(en >> T::kHalf) << (j * W);
+        for (int j = 0; j < L; ++j) {
+            const Entry en = slices[lane * L + j];
+            u0 |= (uint64_t)(en & (Entry)S::kField) << (j * W);
+            u1 |= (uint64_t)(en >> T::kHalf) << (j * W);
+        }
     }
     const uint64_t g = tile * kWave + lane;
     const uint64_t zg = seedB + (g * (uint64_t)S::kWordsPerGroup + 1) * kGamma;
@@ -236,23 +252,31 @@ tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t 
     wave_sync();
 
     // ---- owners: pick up the verdict of each element's group, finish, store ---------------------
+    const uint64_t zA0 = seedA + (6 * (tile0 + 2 * (uint64_t)lane) + 1) * kGamma;   // A[6i] of the lane's first element
 #pragma unroll
     for (int c = 0; c < T::kPairs; ++c) {
         const int e = 2 * (c * kWave + lane);
         if (e < T::kTile) {
             const uint64_t i = tile0 + e;
             Pair r[2];
+            const int grp0 = e / L, j0 = e - grp0 * L;
+            const U64x2 v0 = verdict[grp0];
+            // both elements of the pair sit in one group unless L is odd and the pair straddles two
+            const bool split = (L % 2 != 0) && (j0 == L - 1);
+            const U64x2 v1 = split ? verdict[grp0 + 1] : v0;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int eh = e + h;
-                const int grp = eh / L, j = eh - grp * L;
-                const U64x2 v = verdict[grp];
-                const Pair sign{(v.a >> (j * W)) & 1, (v.a >> (j * W + 1)) & 1};
+                const U64x2 v = h ? v1 : v0;
+                const int j = h ? (split ? 0 : j0 + 1) : j0;
+                // only bits 0 and 1 of each shifted word are used
+                const uint32_t sg = (uint32_t)(v.a >> (j * W));
+                const Pair sign{sg & 1u, (sg >> 1) & 1u};
                 if (MODE == kSign) {
                     r[h] = sign;
                 } else {
-                    const Pair rho{(v.b >> (2 * j)) & 1, (v.b >> (2 * j + 1)) & 1};
-                    const uint64_t zA = seedA + (6 * (i + h) + 1) * kGamma;
+                    const uint32_t rh = (uint32_t)(v.b >> (2 * j));
+                    const Pair rho{rh & 1u, (rh >> 1) & 1u};
+                    const uint64_t zA = zA0 + (uint64_t)(6 * (2 * c * kWave + h)) * kGamma;
                     const Pair D = b2a_drelu(sign, rho, zA);
                     r[h] = (MODE == kDrelu) ? D : beaver_mul(Pair{h ? xa[c].b : xa[c].a, h ? xb[c].b : xb[c].a}, D, zA);
                 }
@@ -266,6 +290,55 @@ tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t 
             }
         }
     }
+}
+
+template <int W, int MODE>
+__global__ void __launch_bounds__(kBlock)
+tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t *o0,
+            uint64_t *o1)
+{
+    using T = TileTraits<W>;
+    __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][T::kSliceBytes];
+    __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];     // per group: {sign shares, B2A dealer word}
+    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
+    if (tile * T::kTile >= n) return;        // whole wavefront beyond the tensor (uniform per wave)
+    tile_body<W, MODE>(x0, x1, n, k, seedB, seedA, o0, o1, tile, lane, slices_all[wv], verdict_all[wv]);
+}
+
+// Several tensors of one slice width in a single launch.  The descriptors travel in the kernel
+// argument block; wave-tiles of all tensors are numbered consecutively and tile_end[t] is the number
+// of wave-tiles in tensors 0..t.
+constexpr int kBatchMax = 24;
+
+struct BatchTensor {
+    const uint64_t *x0, *x1;
+    uint64_t *o0, *o1;
+    uint64_t n, seedB, seedA;
+    int k, pad;
+};
+
+struct BatchArgs {
+    int count, pad;
+    uint64_t tile_end[kBatchMax];
+    BatchTensor t[kBatchMax];
+};
+
+template <int W, int MODE>
+__global__ void __launch_bounds__(kBlock)
+tile_batch_kernel(const BatchArgs args)
+{
+    using T = TileTraits<W>;
+    __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][T::kSliceBytes];
+    __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];
+    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const uint64_t gt = (uint64_t)blockIdx.x * kWavesPerBlock + wv;          // wave-tile number over the whole batch
+    if (gt >= args.tile_end[args.count - 1]) return;
+    int ti = 0;
+    while (gt >= args.tile_end[ti]) ++ti;                                     // uniform per wave, at most kBatchMax steps
+    const uint64_t tile = gt - (ti ? args.tile_end[ti - 1] : 0);
+    const BatchTensor &d = args.t[ti];
+    tile_body<W, MODE>(d.x0, d.x1, d.n, d.k, d.seedB, d.seedA, d.o0, d.o1, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 }  // namespace hb

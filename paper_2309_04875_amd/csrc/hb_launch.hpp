@@ -6,13 +6,19 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "hb_kernels.hpp"
+
 namespace hb {
 
 using GroupLauncher = hipError_t (*)(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t seedB,
                                      uint64_t seedA, uint64_t *o0, uint64_t *o1, bool vec16, hipStream_t stream);
 
+// Launches the tensors described by `args` (all of one slice width, tile-kernel eligible) in one grid.
+using BatchLauncher = hipError_t (*)(const BatchArgs &args, hipStream_t stream);
+
 struct LauncherTable {
-    GroupLauncher f[3][64];   // [mode][w - 1]
+    GroupLauncher f[3][64];       // [mode][w - 1]
+    BatchLauncher batch[3][64];   // null where the width has no tile kernel
 };
 
 LauncherTable &launcher_table();

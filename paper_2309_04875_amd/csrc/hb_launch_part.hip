@@ -37,10 +37,25 @@ hipError_t launch_group(const uint64_t *x0, const uint64_t *x1, uint64_t n, int 
     return hipGetLastError();
 }
 
+template <int W, int MODE>
+hipError_t launch_batch(const hb::BatchArgs &args, hipStream_t stream)
+{
+    if constexpr (hb::TileTraits<W>::kSupported) {
+        const uint64_t wave_tiles = args.tile_end[args.count - 1];
+        const uint64_t blocks = (wave_tiles + hb::kWavesPerBlock - 1) / hb::kWavesPerBlock;
+        if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+        hipLaunchKernelGGL((hb::tile_batch_kernel<W, MODE>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, stream, args);
+        return hipGetLastError();
+    } else {
+        return hipErrorInvalidDeviceFunction;
+    }
+}
+
 template <int W>
 void fill(hb::LauncherTable &t)
 {
     t.f[HB_PART_MODE][W - 1] = &launch_group<W, HB_PART_MODE>;
+    t.batch[HB_PART_MODE][W - 1] = hb::TileTraits<W>::kSupported ? &launch_batch<W, HB_PART_MODE> : nullptr;
     if constexpr (W < HB_PART_HI) fill<W + 1>(t);
 }
 

@@ -75,11 +75,12 @@ __device__ __forceinline__ Pair beaver_and(uint64_t zq, Pair U, Pair V)
     const uint64_t b0 = mix64(zq + 2 * kGamma);
     const uint64_t b1 = mix64(zq + 3 * kGamma);
     const uint64_t c0 = mix64(zq + 4 * kGamma);
-    const uint64_t c1 = ((a0 ^ a1) & (b0 ^ b1)) ^ c0;           // dealer completes the triple
-    const uint64_t d = (U.p0 ^ a0) ^ (U.p1 ^ a1);               // each party sends U_p ^ a_p
-    const uint64_t e = (V.p0 ^ b0) ^ (V.p1 ^ b1);
+    const uint64_t a = a0 ^ a1, b = b0 ^ b1;                    // the dealer's triple (a, b, a & b)
+    const uint64_t c1 = (a & b) ^ c0;                           // dealer completes the sharing of c
+    const uint64_t d = (U.p0 ^ U.p1) ^ a;                       // opened: XOR of what each party sends, U_p ^ a_p
+    const uint64_t e = (V.p0 ^ V.p1) ^ b;                       // opened: XOR of V_p ^ b_p
     Pair Z;
-    Z.p0 = c0 ^ (d & b0) ^ (e & a0) ^ (d & e);
+    Z.p0 = c0 ^ (d & (b0 ^ e)) ^ (e & a0);                      // = c0 ^ (d & b0) ^ (e & a0) ^ (d & e)
     Z.p1 = c1 ^ (d & b1) ^ (e & a1);
     return Z;
 }

@@ -13,10 +13,17 @@ LIBRARY = os.path.join(HERE, "libhb.so")
 HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP = 0, -1, -2, -3
 BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accounting
 
-EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_tensor_seed", "hb_opened_bits",
-           "hb_strerror", "hb_last_hip_error")
+EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_tensor_seed",
+           "hb_opened_bits", "hb_strerror", "hb_last_hip_error")
 
 _lib = None
+
+
+class hb_tensor(ctypes.Structure):
+    """Mirror of `struct hb_tensor` in include/hb.h."""
+    _fields_ = [("share0", ctypes.c_void_p), ("share1", ctypes.c_void_p), ("out0", ctypes.c_void_p),
+                ("out1", ctypes.c_void_p), ("n", ctypes.c_size_t), ("k", ctypes.c_int), ("m", ctypes.c_int),
+                ("seed", ctypes.c_uint64)]
 
 
 class HbError(RuntimeError):
@@ -40,6 +47,10 @@ def load():
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [vp, vp, sz, ci, ci, u64, vp, vp, u64p, vp]
+    for name in ("hb_relu_batch", "hb_drelu_batch"):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [ctypes.POINTER(hb_tensor), sz, u64p, vp]
     lib.hb_open.restype = ci
     lib.hb_open.argtypes = [vp, vp, sz, ci, vp, vp]
     lib.hb_tensor_seed.restype = u64
@@ -115,6 +126,34 @@ def hb_relu(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
 def hb_sign_shares(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
     """XOR shares (0/1) of the sign bit after the adder circuit; returns (out0, out1, opened_bits)."""
     return _shares_call("hb_sign_shares", share0, share1, k, m, seed, out0, out1, stream)
+
+
+def make_batch(items):
+    """ctypes descriptor array for a batched call; items: (share0, share1, out0, out1, k, m, seed) with torch tensors."""
+    arr = (hb_tensor * len(items))()
+    for d, (s0, s1, o0, o1, k, m, seed) in zip(arr, items):
+        d.n = _tensor_args(s0, s1, o0, o1)
+        d.share0, d.share1, d.out0, d.out1 = s0.data_ptr(), s1.data_ptr(), o0.data_ptr(), o1.data_ptr()
+        d.k, d.m, d.seed = int(k), int(m), int(seed) & (2**64 - 1)
+    return arr
+
+
+def _batch_call(name, batch, stream):
+    if not isinstance(batch, ctypes.Array):
+        batch = make_batch(batch)
+    bits = ctypes.c_uint64(0)
+    _check(getattr(load(), name)(batch, len(batch), ctypes.byref(bits), _stream_handle(stream)))
+    return int(bits.value)
+
+
+def hb_relu_batch(batch, stream=None):
+    """hb_relu over a set of tensors (list of (share0, share1, out0, out1, k, m, seed) or a make_batch array);
+    returns the total opened bits."""
+    return _batch_call("hb_relu_batch", batch, stream)
+
+
+def hb_drelu_batch(batch, stream=None):
+    return _batch_call("hb_drelu_batch", batch, stream)
 
 
 def hb_open(share0, share1, binary=False, out=None, stream=None):

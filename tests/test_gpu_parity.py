@@ -189,6 +189,98 @@ def test_resnet18_imagenet_batch64_full_size():
 
 
 # ----------------------------------------------------------------------------------------------
+# batched entry points: same shares as the per-tensor calls, i.e. as the oracle
+# ----------------------------------------------------------------------------------------------
+
+def _batch_against_oracle(specs, root, relu=True, extra=None):
+    items, expect = [], []
+    for spec in specs:
+        x, s0, s1 = workloads.materialize(spec)
+        seed = hb.hb_tensor_seed(root, spec.tensor_id)
+        d0, d1 = _dev(s0), _dev(s1)
+        items.append((d0, d1, torch.empty_like(d0), torch.empty_like(d1), spec.k, spec.m, seed))
+        expect.append((oracle.relu if relu else oracle.drelu)(s0, s1, spec.k, spec.m, seed))
+    if extra:
+        items.extend(extra)
+    bits = (hb.hb_relu_batch if relu else hb.hb_drelu_batch)(items)
+    for (d0, d1, o0, o1, k, m, seed), (e0, e1, _) in zip(items, expect):
+        assert np.array_equal(_host(o0), e0) and np.array_equal(_host(o1), e1), (k, m)
+    return bits, sum(e[2] for e in expect)
+
+
+def test_batch_resnet18_cifar_one_image_set():
+    for relu in (True, False):
+        bits, ebits = _batch_against_oracle(workloads.resnet18_cifar(), SEED, relu)
+        assert bits == ebits
+
+
+def test_batch_mixed_widths_ragged_and_unaligned():
+    """Widths with and without a tile kernel, odd sizes, an 8-byte-aligned tensor, an empty tensor, more
+    tensors of one width than one launch holds."""
+    rng = np.random.default_rng(91)
+    specs = []
+    shapes = [(1000,), (1,), (513,), (4096,), (77,), (0,), (2049,)]
+    kms = [(12, 20), (8, 14), (8, 18), (0, 64), (5, 12), (12, 20), (3, 4), (8, 12)]
+    t = 0
+    for rep in range(5):
+        for shape in shapes:
+            k, m = kms[t % len(kms)]
+            specs.append(workloads.TensorSpec("mixed", t, shape, k, m, 2.0, "normal", 900 + t))
+            t += 1
+    specs += [workloads.TensorSpec("mixed", t + i, (300 + i,), 12, 20, 1.0, "normal", 990 + i) for i in range(30)]
+    # one more tensor whose buffers are only 8-byte aligned
+    s0, s1 = _rand_shares(rng, 1235)
+    d0, d1 = _dev(s0)[1:], _dev(s1)[1:]
+    o0 = torch.empty(1235, dtype=torch.int64, device=DEV)[1:]
+    o1 = torch.empty(1235, dtype=torch.int64, device=DEV)[1:]
+    extra = [(d0, d1, o0, o1, 12, 20, 4242)]
+    bits, ebits = _batch_against_oracle(specs, SEED + 5, True, extra)
+    e0, e1, b = oracle.relu(s0[1:], s1[1:], 12, 20, 4242)
+    assert np.array_equal(_host(o0), e0) and np.array_equal(_host(o1), e1)
+    assert bits == ebits + b
+
+
+def test_batch_full_size_headline_matches_per_tensor_calls():
+    """Batch-512 set in one batched call (the launch configuration the benchmark times) against the
+    per-tensor entry point, every element, and against the oracle on sampled elements."""
+    rng = np.random.default_rng(6)
+    specs = workloads.resnet18_cifar_batch512()
+    items, keep = [], []
+    for spec in specs[::4]:          # 5 of the 17 tensors keep the memory footprint of the test modest
+        x, s0, s1 = workloads.materialize_on_device(spec, DEV)
+        seed = hb.hb_tensor_seed(SEED, spec.tensor_id)
+        items.append((s0, s1, torch.empty_like(s0), torch.empty_like(s1), spec.k, spec.m, seed))
+        keep.append(spec)
+    hb.hb_relu_batch(items)
+    for spec, (s0, s1, o0, o1, k, m, seed) in zip(keep, items):
+        r0, r1, _ = hb.hb_relu(s0, s1, k, m, seed)
+        assert torch.equal(r0, o0) and torch.equal(r1, o1), spec
+        idx = _sample_indices(spec.n, 8, rng, 1 << 14)
+        tidx = torch.from_numpy(idx).to(DEV)
+        e0, e1 = oracle.evaluate_at(_host(s0[tidx]), _host(s1[tidx]), idx.astype(np.uint64), k, m, seed, oracle.WHAT_RELU)
+        assert np.array_equal(_host(o0[tidx]), e0) and np.array_equal(_host(o1[tidx]), e1), spec
+
+
+def test_batch_errors():
+    n = 512
+    t = [torch.zeros(n, dtype=torch.int64, device=DEV) for _ in range(8)]
+    good = [(t[0], t[1], t[2], t[3], 12, 20, 1), (t[4], t[5], t[6], t[7], 8, 14, 2)]
+    assert hb.hb_relu_batch(good) == n * (241 + 213)
+    assert hb.hb_relu_batch([]) == 0
+    arr = hb.make_batch(good)
+    arr[1].m = 8                                     # bad slice in the second tensor
+    assert hb.raw("hb_relu_batch", arr, 2, None, None) == hb.HB_EINVAL
+    arr = hb.make_batch(good)
+    arr[1].out0 = arr[0].share0                      # output of one tensor over an input of another
+    assert hb.raw("hb_relu_batch", arr, 2, None, None) == hb.HB_EINVAL
+    arr = hb.make_batch(good)
+    arr[0].share1 = arr[0].share1 + 4
+    assert hb.raw("hb_relu_batch", arr, 2, None, None) == hb.HB_EALIGN
+    assert hb.raw("hb_relu_batch", None, 2, None, None) == hb.HB_EINVAL
+    torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------------------
 # boundary behaviour
 # ----------------------------------------------------------------------------------------------
 
