@@ -23,6 +23,16 @@ ROOT_SEED = 0x2309048750000001
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 BYTES_PER_ELEMENT = 32         # two int64 shares read, two written
 
+# HBM traffic of one launch of hb::tile_batch_kernel<8, relu> on this workload, from the rocprofv3 --pmc runs
+# summarised in profiles/tile_batch_kernel_w8_relu_resnet18_b512.txt: FETCH_SIZE 2228373.0 KiB scaled by 2.0
+# (what the counter under-reads for a plain streaming kernel of known size), WRITE_SIZE 4456448.0 KiB scaled by 1.0.
+PROFILED_TRAFFIC_BYTES = (2228373.0 * 2.0 + 4456448.0 * 1.0) * 1024.0
+PROFILED_ELEMENTS = 285212672
+# Vector-ALU instructions per wavefront of the same kernel (SQ_INSTS_VALU / SQ_WAVES, profiles/
+# tile_kernel_w8_w64_valu_counters.txt); a wavefront covers 512 elements.
+VALU_INSTS_PER_WAVE = 2193.0
+VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9      # CUs x SIMDs x lanes per clock x 2.4 GHz = 39.3e12 32-bit lane-ops/s
+
 
 def _time_launches(fn, reps, torch):
     """Average duration in ms of `fn` (one launch) over `reps` launches, by events on the current stream."""
@@ -97,6 +107,7 @@ def main():
     kernel_ms_per_step = avg_launch_ms
     bytes_per_launch = BYTES_PER_ELEMENT * n_total
     achieved_gbs = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
+    valu_lane_ops = VALU_INSTS_PER_WAVE * 64.0 * (n_total / 512.0)     # instructions x lanes x wavefronts
 
     # ---- side figures, outside the timed region ---------------------------------------------
     spec0, s0, s1, o0, o1, seed0 = tensors[0]
@@ -150,10 +161,19 @@ def main():
                    "elements": n_total, "k": k, "m": m, "launches_per_step": 1, "tensors_per_step": len(tensors),
                    "root_seed": ROOT_SEED},
         "roofline": {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved_gbs / HBM_PEAK_GBS,
+                     "traffic": PROFILED_TRAFFIC_BYTES if n_total == PROFILED_ELEMENTS else None,
+                     "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                     "algorithmic_bytes_per_launch": bytes_per_launch,
                      "kernel": "hb::tile_batch_kernel<8, relu>",
                      "avg_launch_ms": avg_launch_ms, "kernel_ms_per_step": kernel_ms_per_step,
                      "algorithmic_bytes_per_element": BYTES_PER_ELEMENT},
+        # the kernel is bound by vector-ALU issue (VALUBusy 96 %), so the HBM fraction above cannot reach 1;
+        # this is the same launch priced against the chip's 32-bit integer lane-op rate
+        "roofline_alu": {"bound": "alu", "achieved": valu_lane_ops / (avg_launch_ms * 1e-3) / 1e12,
+                         "peak": VALU_PEAK_LANE_OPS / 1e12, "unit": "T lane-ops/s",
+                         "frac": valu_lane_ops / (avg_launch_ms * 1e-3) / VALU_PEAK_LANE_OPS,
+                         "valu_instructions_per_element": VALU_INSTS_PER_WAVE / 512.0},
         "cpu_baseline": cpu,
         "extra": extra,
     }
