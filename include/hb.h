@@ -105,6 +105,22 @@ typedef struct hb_tensor {
 HB_API int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream);
 HB_API int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream);
 
+/*
+ * Zero-error search for the high cut (Sec. 4.1.2, the "eco" strategy: try every high cut with no low cut
+ * and see whether any DReLU result changes).  counts[m - 1] receives the number of elements whose DReLU
+ * on the slice [0, m) differs from DReLU on the full ring, for m = 1 .. 64 (counts[63] is always 0).
+ * share0, share1: device, n int64 each.  counts: DEVICE pointer to 64 uint64 (8-byte aligned), overwritten;
+ * it must not overlap the shares.  Two kernels are enqueued on `stream` (clear, then scan).
+ */
+HB_API int hb_eco_scan(const int64_t *share0, const int64_t *share1, size_t n, uint64_t *counts, void *stream);
+
+/*
+ * The eco choice from a scan: the smallest m such that no m' >= m has a mismatch, i.e. the fewest bits
+ * [0, m) that reproduce the full-ring DReLU on every scanned element (Theorem 1).  counts: HOST pointer
+ * to the 64 values read back from hb_eco_scan.  Returns m in [1, 64], or HB_EINVAL for a null pointer.
+ */
+HB_API int hb_eco_choose(const uint64_t *counts);
+
 /* Seed of tensor `tensor_id` in a set of tensors keyed by one root seed (host-only, no GPU work). */
 HB_API uint64_t hb_tensor_seed(uint64_t root_seed, uint64_t tensor_id);
 

@@ -45,6 +45,10 @@ def lib():
         L.hb_ref_drelu.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _int, _i64p, _i64p, _u64p]
         L.hb_ref_relu.restype = _int
         L.hb_ref_relu.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _int, _i64p, _i64p, _u64p]
+        L.hb_ref_eco_scan.restype = _int
+        L.hb_ref_eco_scan.argtypes = [_i64p, _i64p, _u64, _u64, _int, _u64p]
+        L.hb_ref_eco_choose.restype = _int
+        L.hb_ref_eco_choose.argtypes = [_u64p, _int]
         L.hb_ref_open.restype = _int
         L.hb_ref_open.argtypes = [_i64p, _i64p, _u64, _int, _int, _i64p]
         _lib = L
@@ -162,3 +166,18 @@ def open_shares(share0, share1, binary=False, ring_bits=64):
     if st != 0:
         raise ValueError("oracle rejected arguments (status %d)" % st)
     return out
+
+
+def eco_scan(share0, share1, seed=1, ring_bits=64):
+    """counts[m-1] = elements whose DReLU on [0, m) differs from the full ring, by running the protocol for every m."""
+    s0, s1 = _as_i64(share0), _as_i64(share1)
+    counts = np.zeros(64, dtype=np.uint64)
+    st = lib().hb_ref_eco_scan(_ptr(s0), _ptr(s1), _u64(s0.size), _u64(seed), ring_bits, _ptr(counts, _u64p))
+    if st != 0:
+        raise ValueError("oracle rejected arguments (status %d)" % st)
+    return counts
+
+
+def eco_choose(counts, ring_bits=64):
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    return int(lib().hb_ref_eco_choose(_ptr(c, _u64p), ring_bits))

@@ -323,3 +323,38 @@ int hb_ref_open(const int64_t *share0, const int64_t *share1, uint64_t n, int bi
     }
     return HB_REF_OK;
 }
+
+/* ------------------------------------------------------------------ */
+/* Zero-error search for the high cut ("eco" strategy, Sec. 4.1.2):     */
+/* evaluate DReLU on [0, m) for every m and see whether the result      */
+/* differs from the full ring.  counts[m-1] = number of elements whose  */
+/* reconstructed DReLU at (0, m) differs from the one at (0, N).        */
+/* ------------------------------------------------------------------ */
+int hb_ref_eco_scan(const int64_t *share0, const int64_t *share1, uint64_t n, uint64_t seed, int ring_bits,
+                    uint64_t *counts)
+{
+    shape_t full, cut;
+    uint64_t i;
+    int m;
+    if (!counts || make_shape(&full, 0, ring_bits, seed, ring_bits) != HB_REF_OK) return HB_REF_EINVAL;
+    if (n > 0 && (!share0 || !share1)) return HB_REF_EINVAL;
+    for (m = 1; m <= 64; m++) counts[m - 1] = 0;
+    for (m = 1; m <= ring_bits; m++) {
+        if (make_shape(&cut, 0, m, seed, ring_bits) != HB_REF_OK) return HB_REF_EINVAL;
+        for (i = 0; i < n; i++) {
+            elem_t a, b;
+            eval_element(&full, i, (uint64_t)share0[i], (uint64_t)share1[i], 0, &a);
+            eval_element(&cut, i, (uint64_t)share0[i], (uint64_t)share1[i], 0, &b);
+            if (((a.drelu[0] + a.drelu[1]) & full.ring) != ((b.drelu[0] + b.drelu[1]) & full.ring)) counts[m - 1]++;
+        }
+    }
+    return HB_REF_OK;
+}
+
+/* The zero-error choice: the smallest m such that no m' >= m shows a mismatch. */
+int hb_ref_eco_choose(const uint64_t *counts, int ring_bits)
+{
+    int m = ring_bits;
+    while (m > 1 && counts[m - 2] == 0) m--;
+    return m;
+}

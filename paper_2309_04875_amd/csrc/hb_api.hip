@@ -9,6 +9,7 @@
 #include <cstring>
 #include <utility>
 
+#include "hb_eco.hpp"
 #include "hb_kernels.hpp"
 #include "hb_launch.hpp"
 
@@ -269,6 +270,56 @@ int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits,
 int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
 {
     return run_batch(hb::kDrelu, tensors, count, opened_bits, stream);
+}
+
+int hb_eco_scan(const int64_t *share0, const int64_t *share1, size_t n, uint64_t *counts, void *stream)
+{
+    if (counts == nullptr) return HB_EINVAL;
+    if (((uintptr_t)counts & 7u) != 0) return HB_EALIGN;
+    const void *ptrs[2] = {share0, share1};
+    int st = check_common(ptrs, 2, n);
+    if (st != HB_OK) return st;
+    st = check_device_buffer(counts, 64);
+    if (st != HB_OK) return st;
+    if (n > 0) {
+        const Range c = range_of(counts, 64);
+        if (!disjoint(c, range_of(share0, n)) || !disjoint(c, range_of(share1, n))) return HB_EINVAL;
+    }
+    hipLaunchKernelGGL(hb::eco_zero_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (unsigned long long *)counts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    if (n == 0) return HB_OK;
+    // aim at about 2048 wavefronts; a lane takes `chunks` carry-save trees of 64 elements
+    uint64_t per_lane = ((uint64_t)n + 2048ull * 64 - 1) / (2048ull * 64);
+    uint64_t chunks = (per_lane + hb::kEcoChunk - 1) / hb::kEcoChunk;
+    if (chunks < 1) chunks = 1;
+    if (chunks > (uint64_t)hb::kEcoMaxPerLane / hb::kEcoChunk) chunks = hb::kEcoMaxPerLane / hb::kEcoChunk;
+    const uint64_t per_wave = (uint64_t)hb::kWave * hb::kEcoChunk * chunks;
+    const uint64_t waves = ((uint64_t)n + per_wave - 1) / per_wave;
+    const uint64_t blocks = (waves + hb::kWavesPerBlock - 1) / hb::kWavesPerBlock;
+    if (blocks > 0x7fffffffull) return HB_EINVAL;
+    int live = 1;
+    while ((1ull << live) <= chunks * hb::kEcoChunk) ++live;      // planes that can be non-zero
+    if (all_aligned16(ptrs, 2)) {
+        hipLaunchKernelGGL((hb::eco_scan_kernel<true>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, (hipStream_t)stream,
+                           (const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, (int)chunks, live,
+                           (unsigned long long *)counts);
+    } else {
+        hipLaunchKernelGGL((hb::eco_scan_kernel<false>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, (hipStream_t)stream,
+                           (const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, (int)chunks, live,
+                           (unsigned long long *)counts);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return HB_OK;
+}
+
+int hb_eco_choose(const uint64_t *counts)
+{
+    if (counts == nullptr) return HB_EINVAL;
+    int m = 64;
+    while (m > 1 && counts[m - 2] == 0) --m;
+    return m;
 }
 
 int hb_open(const int64_t *share0, const int64_t *share1, size_t n, int binary, int64_t *out, void *stream)

@@ -13,7 +13,8 @@ LIBRARY = os.path.join(HERE, "libhb.so")
 HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP = 0, -1, -2, -3
 BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accounting
 
-EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_tensor_seed",
+EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_eco_scan", "hb_eco_choose",
+           "hb_tensor_seed",
            "hb_opened_bits", "hb_strerror", "hb_last_hip_error")
 
 _lib = None
@@ -51,6 +52,10 @@ def load():
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [ctypes.POINTER(hb_tensor), sz, u64p, vp]
+    lib.hb_eco_scan.restype = ci
+    lib.hb_eco_scan.argtypes = [vp, vp, sz, vp, vp]
+    lib.hb_eco_choose.restype = ci
+    lib.hb_eco_choose.argtypes = [u64p]
     lib.hb_open.restype = ci
     lib.hb_open.argtypes = [vp, vp, sz, ci, vp, vp]
     lib.hb_tensor_seed.restype = u64
@@ -154,6 +159,28 @@ def hb_relu_batch(batch, stream=None):
 
 def hb_drelu_batch(batch, stream=None):
     return _batch_call("hb_drelu_batch", batch, stream)
+
+
+def hb_eco_scan(share0, share1, counts=None, stream=None):
+    """counts[m-1] = elements whose DReLU on [0, m) differs from the full ring; returns the 64-entry device tensor."""
+    import torch
+    if counts is None:
+        counts = torch.empty(64, dtype=torch.int64, device=share0.device)
+    n = _tensor_args(share0, share1)
+    if counts.dtype != torch.int64 or counts.numel() != 64 or not counts.is_cuda or not counts.is_contiguous():
+        raise TypeError("counts must be a contiguous int64 CUDA tensor of 64 entries")
+    _check(load().hb_eco_scan(share0.data_ptr(), share1.data_ptr(), n, counts.data_ptr(), _stream_handle(stream)))
+    return counts
+
+
+def hb_eco_choose(counts):
+    """Smallest m with no mismatch at any m' >= m; counts: 64 host integers (or a tensor, copied to the host)."""
+    if hasattr(counts, "cpu"):
+        counts = counts.cpu().tolist()
+    arr = (ctypes.c_uint64 * 64)(*[int(c) & (2**64 - 1) for c in counts])
+    m = load().hb_eco_choose(arr)
+    _check(m if m < 0 else HB_OK)
+    return m
 
 
 def hb_open(share0, share1, binary=False, out=None, stream=None):

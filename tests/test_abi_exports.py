@@ -53,3 +53,16 @@ def test_strerror_texts():
     for st in (-1, -2, -3, -99):
         assert hb.strerror(st)
     assert hb.last_hip_error() == ""
+
+
+def test_eco_choose_matches_oracle():
+    import ctypes
+    import numpy as np
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        c = np.zeros(64, dtype=np.uint64)
+        top = int(rng.integers(0, 63))
+        c[:top] = rng.integers(0, 5, top)
+        arr = (ctypes.c_uint64 * 64)(*[int(v) for v in c])
+        assert hb.raw("hb_eco_choose", arr) == oracle.eco_choose(c)
+    assert hb.raw("hb_eco_choose", None) == hb.HB_EINVAL

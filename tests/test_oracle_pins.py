@@ -402,3 +402,54 @@ def test_output_shares_look_uniform_and_depend_on_seed():
         p0, p1 = oracle.evaluate(s0, s1, 12, 20, SEED + 1, what)
         assert (p0 != o0).mean() > 0.99
         assert np.array_equal(p0 + p1, o0 + o1)
+
+
+# ----------------------------------------------------------------------------------------------
+# zero-error high-cut scan (Sec. 4.1.2, "eco")
+# ----------------------------------------------------------------------------------------------
+
+def _bit_disagreement_counts(x):
+    """#{i : bit (m-1) of x_i differs from its sign bit}, m = 1..64 -- what Theorem 1's proof says decides the
+    outcome at (0, m): the slices are exact shares of x mod 2^m, so only the sign bit read changes."""
+    ux = x.view(np.uint64)
+    sign = ux >> np.uint64(63)
+    return np.array([int((((ux >> np.uint64(m - 1)) & np.uint64(1)) != sign).sum()) for m in range(1, 65)], dtype=np.uint64)
+
+
+def test_eco_scan_counts_sign_bit_disagreements():
+    rng = np.random.default_rng(41)
+    x = np.concatenate([np.rint(rng.standard_normal(700) * 2 * 65536).astype(np.int64),
+                        rng.integers(np.iinfo(np.int64).min, np.iinfo(np.int64).max, 100, dtype=np.int64),
+                        np.array([0, -1, 1, np.iinfo(np.int64).min, np.iinfo(np.int64).max], dtype=np.int64)])
+    s0, s1 = _shares_of(x, rng)
+    counts = oracle.eco_scan(s0, s1, seed=SEED)
+    assert np.array_equal(counts, _bit_disagreement_counts(x))
+    assert counts[63] == 0
+
+
+def test_eco_choice_is_theorem1_bound():
+    """For values in [-2^(t-1), 2^(t-1)) that reach both ends, the zero-error cut is exactly m = t."""
+    rng = np.random.default_rng(42)
+    for t in (3, 12, 19, 22, 40):
+        lo, hi = -(1 << (t - 1)), (1 << (t - 1))
+        x = rng.integers(lo, hi, 300, dtype=np.int64)
+        x[:2] = [lo, hi - 1]
+        s0, s1 = _shares_of(x, rng)
+        counts = oracle.eco_scan(s0, s1)
+        assert (counts[t - 1:] == 0).all()
+        assert counts[t - 2] > 0                       # one bit less already flips the extremes
+        assert oracle.eco_choose(counts) == t
+    assert oracle.eco_choose(np.zeros(64, dtype=np.uint64)) == 1
+    c = np.zeros(64, dtype=np.uint64)
+    c[62] = 5
+    assert oracle.eco_choose(c) == 64
+
+
+def test_eco_scan_small_ring_brute_force():
+    v = np.arange(256, dtype=np.int64)
+    s0, s1 = [a.reshape(-1) for a in np.meshgrid(v, v, indexing="ij")]
+    counts = oracle.eco_scan(s0[::7], s1[::7], ring_bits=8)
+    xs = (s0[::7] + s1[::7]) & 255
+    for m in range(1, 9):
+        assert counts[m - 1] == int((((xs >> (m - 1)) & 1) != (xs >> 7)).sum())
+    assert (counts[8:] == 0).all()
