@@ -127,6 +127,11 @@ def main():
         extra["drelu_w8_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         ms = _time_launches(lambda: hb.hb_open(s0, s1, False, out=o0), 300, torch)
         extra["open_copy_ceiling_gbs"] = 24 * spec0.n / (ms * 1e-3) / 1e9
+        counts = torch.empty(64, dtype=torch.int64, device=dev)
+        ms = _time_launches(lambda: hb.hb_eco_scan(s0, s1, counts), 300, torch)
+        extra["eco_scan_elems_per_s"] = spec0.n / (ms * 1e-3)
+        extra["eco_scan_hbm_frac"] = 16 * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS      # 16 B read per element
+        extra["eco_scan_zero_error_m"] = hb.hb_eco_choose(counts)
 
     # ---- CPU baseline: the oracle as it stands on this machine's host cores, bounded sample ------
     cpu = None
@@ -173,7 +178,7 @@ def main():
         "roofline_alu": {"bound": "alu", "achieved": valu_lane_ops / (avg_launch_ms * 1e-3) / 1e12,
                          "peak": VALU_PEAK_LANE_OPS / 1e12, "unit": "T lane-ops/s",
                          "frac": valu_lane_ops / (avg_launch_ms * 1e-3) / VALU_PEAK_LANE_OPS,
-                         "valu_instructions_per_element": VALU_INSTS_PER_WAVE / 512.0},
+                         "valu_instructions_per_element": VALU_INSTS_PER_WAVE / 8.0},
         "cpu_baseline": cpu,
         "extra": extra,
     }

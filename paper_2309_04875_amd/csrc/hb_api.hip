@@ -289,8 +289,11 @@ int hb_eco_scan(const int64_t *share0, const int64_t *share1, size_t n, uint64_t
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     if (n == 0) return HB_OK;
-    // aim at about 2048 wavefronts; a lane takes `chunks` carry-save trees of 64 elements
-    uint64_t per_lane = ((uint64_t)n + 2048ull * 64 - 1) / (2048ull * 64);
+    // aim at about 1024 wavefronts (one block per CU: the per-wave epilogue and the 64 atomics per block are
+    // fixed costs, and 4 waves per CU with 64 loads in flight each already stream at 4.4 TB/s);
+    // a lane takes `chunks` carry-save trees of 64 elements
+    const uint64_t target_waves = 1024;
+    uint64_t per_lane = ((uint64_t)n + target_waves * 64 - 1) / (target_waves * 64);
     uint64_t chunks = (per_lane + hb::kEcoChunk - 1) / hb::kEcoChunk;
     if (chunks < 1) chunks = 1;
     if (chunks > (uint64_t)hb::kEcoMaxPerLane / hb::kEcoChunk) chunks = hb::kEcoMaxPerLane / hb::kEcoChunk;
