@@ -49,6 +49,10 @@ def lib():
         L.hb_ref_eco_scan.argtypes = [_i64p, _i64p, _u64, _u64, _int, _u64p]
         L.hb_ref_eco_choose.restype = _int
         L.hb_ref_eco_choose.argtypes = [_u64p, _int]
+        L.hb_ref_wire_words.restype = _u64
+        L.hb_ref_wire_words.argtypes = [_u64, _int, _int]
+        L.hb_ref_relu_wire.restype = _int
+        L.hb_ref_relu_wire.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _u64p, _u64p]
         L.hb_ref_open.restype = _int
         L.hb_ref_open.argtypes = [_i64p, _i64p, _u64, _int, _int, _i64p]
         _lib = L
@@ -181,3 +185,20 @@ def eco_scan(share0, share1, seed=1, ring_bits=64):
 def eco_choose(counts, ring_bits=64):
     c = np.ascontiguousarray(counts, dtype=np.uint64)
     return int(lib().hb_ref_eco_choose(_ptr(c, _u64p), ring_bits))
+
+
+def wire_words(n, k, m):
+    return int(lib().hb_ref_wire_words(_u64(n), k, m))
+
+
+def relu_wire(share0, share1, k, m, seed):
+    """The packed words each party sends during one ReLU: (wire0, wire1) as uint64 arrays (layout in hb_ref.c)."""
+    s0, s1 = _as_i64(share0), _as_i64(share1)
+    words = wire_words(s0.size, k, m)
+    w0 = np.zeros(words, dtype=np.uint64)
+    w1 = np.zeros(words, dtype=np.uint64)
+    st = lib().hb_ref_relu_wire(_ptr(s0), _ptr(s1), _u64(s0.size), k, m, _u64(seed & (2**64 - 1)),
+                                _ptr(w0, _u64p), _ptr(w1, _u64p))
+    if st != 0:
+        raise ValueError("oracle rejected arguments (status %d)" % st)
+    return w0, w1

@@ -150,6 +150,10 @@ typedef struct {
     uint64_t sign[2];   /* XOR shares of the MSB of that sum              */
     uint64_t drelu[2];  /* arithmetic shares of 1 - sign on Z_2^N         */
     uint64_t relu[2];   /* arithmetic shares of x * (1 - sign) on Z_2^N   */
+    /* what each party sends for every opening (its masked share), gate q = 0 .. 2R */
+    uint64_t send_d[2][13], send_e[2][13];  /* U_p ^ a_p, V_p ^ b_p of gate q        */
+    uint64_t send_z[2];                     /* sign_p ^ rho_p                         */
+    uint64_t send_eps[2], send_del[2];      /* x_p - a_p, DReLU_p - b_p               */
 } elem_t;
 
 static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
@@ -182,6 +186,8 @@ static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
 
 #define FIELD(q, slot) ((hb_ref_sm(s->seedB, base + 5u * (uint64_t)(q) + (slot)) >> fsh) & mask)
 #define AND_GATE(q, U, V, Z) \
+    t->send_d[0][q] = ((U)[0] ^ FIELD(q, 0)) & mask; t->send_d[1][q] = ((U)[1] ^ FIELD(q, 1)) & mask; \
+    t->send_e[0][q] = ((V)[0] ^ FIELD(q, 2)) & mask; t->send_e[1][q] = ((V)[1] ^ FIELD(q, 3)) & mask; \
     hb_ref_and_gate((U)[0], (U)[1], (V)[0], (V)[1], FIELD(q, 0), FIELD(q, 1), \
                     FIELD(q, 2), FIELD(q, 3), FIELD(q, 4), mask, &(Z)[0], &(Z)[1])
 
@@ -218,6 +224,8 @@ static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
     const uint64_t rho1 = (Wb >> (2 * j + 1)) & 1;
     const uint64_t rbit = rho0 ^ rho1;
     const uint64_t z = t->sign[0] ^ rho0 ^ t->sign[1] ^ rho1;    /* opened */
+    t->send_z[0] = t->sign[0] ^ rho0;
+    t->send_z[1] = t->sign[1] ^ rho1;
     uint64_t rA[2], beta[2];
     rA[0] = hb_ref_sm(s->seedA, 6 * i) & ring;
     rA[1] = (rbit - rA[0]) & ring;
@@ -228,6 +236,7 @@ static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
     t->drelu[1] = (0 - beta[1]) & ring;
 
     t->relu[0] = t->relu[1] = 0;
+    t->send_eps[0] = t->send_eps[1] = t->send_del[0] = t->send_del[1] = 0;
     if (!want_relu) return;
 
     /* Beaver multiply x * DReLU on Z_2^N */
@@ -239,6 +248,10 @@ static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
     const uint64_t c1 = ((a0 + a1) * (b0 + b1) - c0) & ring;
     const uint64_t eps = ((x0 - a0) + (x1 - a1)) & ring;                       /* opened */
     const uint64_t del = ((t->drelu[0] - b0) + (t->drelu[1] - b1)) & ring;     /* opened */
+    t->send_eps[0] = (x0 - a0) & ring;
+    t->send_eps[1] = (x1 - a1) & ring;
+    t->send_del[0] = (t->drelu[0] - b0) & ring;
+    t->send_del[1] = (t->drelu[1] - b1) & ring;
     t->relu[0] = (c0 + eps * b0 + del * a0 + eps * del) & ring;
     t->relu[1] = (c1 + eps * b1 + del * a1) & ring;
 }
@@ -357,4 +370,59 @@ int hb_ref_eco_choose(const uint64_t *counts, int ring_bits)
     int m = ring_bits;
     while (m > 1 && counts[m - 2] == 0) m--;
     return m;
+}
+
+/* ------------------------------------------------------------------ */
+/* What the two parties would put on the wire for one ReLU (Sec. 2.2:   */
+/* every AND, the B2A and the multiply open masked values; Sec. 4.2:    */
+/* the w-bit fields travel packed in 64-bit words).  Party p's wire is  */
+/* an array of 64-bit words in sections:                                */
+/*   gate 0      : 2 words per group  [2g + 0] = U_p^a_p, [2g + 1] = V_p^b_p            */
+/*   round r     : 4 words per group  [4g + 0,1] = G-update gate, [4g + 2,3] = P-update  */
+/*   B2A         : ceil(n/64) words, bit i%64 of word i/64 = sign_p ^ rho_p of element i */
+/*   multiply    : 2 words per element [2i] = x_p - a_p, [2i + 1] = DReLU_p - b_p        */
+/* Field j of a group word sits at bit j*w; bits of no element are 0.   */
+/* ------------------------------------------------------------------ */
+uint64_t hb_ref_wire_words(uint64_t n, int k, int m)
+{
+    shape_t s;
+    if (make_shape(&s, k, m, 0, 64) != HB_REF_OK) return 0;
+    const uint64_t G = (n + (uint64_t)s.L - 1) / (uint64_t)s.L;
+    return 2 * G + 4 * G * (uint64_t)s.R + (n + 63) / 64 + 2 * n;
+}
+
+int hb_ref_relu_wire(const int64_t *share0, const int64_t *share1, uint64_t n, int k, int m, uint64_t seed,
+                     uint64_t *wire0, uint64_t *wire1)
+{
+    shape_t s;
+    uint64_t i, words;
+    int p, r;
+    if (make_shape(&s, k, m, seed, 64) != HB_REF_OK) return HB_REF_EINVAL;
+    if (n > 0 && (!share0 || !share1 || !wire0 || !wire1)) return HB_REF_EINVAL;
+    words = hb_ref_wire_words(n, k, m);
+    for (i = 0; i < words; i++) wire0[i] = wire1[i] = 0;
+    const uint64_t G = (n + (uint64_t)s.L - 1) / (uint64_t)s.L;
+    const uint64_t off_b2a = 2 * G + 4 * G * (uint64_t)s.R, off_mul = off_b2a + (n + 63) / 64;
+    for (i = 0; i < n; i++) {
+        elem_t t;
+        uint64_t *wire[2] = { wire0, wire1 };
+        const uint64_t g = i / (uint64_t)s.L;
+        const unsigned sh = (unsigned)(i % (uint64_t)s.L) * (unsigned)s.w;
+        eval_element(&s, i, (uint64_t)share0[i], (uint64_t)share1[i], 1, &t);
+        for (p = 0; p < 2; p++) {
+            wire[p][2 * g + 0] |= t.send_d[p][0] << sh;
+            wire[p][2 * g + 1] |= t.send_e[p][0] << sh;
+            for (r = 0; r < s.R; r++) {
+                uint64_t *sec = wire[p] + 2 * G + 4 * G * (uint64_t)r;
+                sec[4 * g + 0] |= t.send_d[p][1 + 2 * r] << sh;
+                sec[4 * g + 1] |= t.send_e[p][1 + 2 * r] << sh;
+                sec[4 * g + 2] |= t.send_d[p][2 + 2 * r] << sh;
+                sec[4 * g + 3] |= t.send_e[p][2 + 2 * r] << sh;
+            }
+            wire[p][off_b2a + i / 64] |= t.send_z[p] << (i % 64);
+            wire[p][off_mul + 2 * i + 0] = t.send_eps[p];
+            wire[p][off_mul + 2 * i + 1] = t.send_del[p];
+        }
+    }
+    return HB_REF_OK;
 }
