@@ -106,6 +106,34 @@ HB_API int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opene
 HB_API int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream);
 
 /*
+ * Party-faithful ReLU: the same protocol and dealer material as hb_relu, but every opening goes through
+ * memory the way it would go over the link between two GPUs (Sec. 2.2: each AND, the B2A and the multiply
+ * open masked values; Sec. 4.2: the w-bit fields are packed into 64-bit words before each communication).
+ * Each party is evaluated by its own threads, owns its state and writes the words it sends to its "wire";
+ * a party reads the other wire only for completed rounds (one kernel launch per communication round:
+ * slice + gate 0, R prefix rounds, sign, B2A bits, multiply openings, result).  out0 / out1 are
+ * bit-for-bit the shares hb_relu returns.
+ *
+ * Wire of party p, 64-bit words: [2G: gate 0][4G per round, R rounds][ceil(n/64): B2A][2n: multiply], G =
+ * ceil(n / L) groups of L = min(floor(64/w), 32) elements; in a group word field j sits at bit j*w; word
+ * [2g] / [4g + 0, 2] holds the masked first operand, [2g + 1] / [4g + 1, 3] the masked second operand of the
+ * gate(s); B2A bit i%64 of word i/64 belongs to element i; multiply words [2i], [2i+1] are x_p - a_p and
+ * DReLU_p - b_p.  Bits that belong to no element are zero.  hb_party_wire_words gives the word count
+ * (8 bytes each; 64 x words = opened bits when w*L = 64 and 64 divides n).
+ *
+ * workspace: DEVICE memory, 256-byte aligned, hb_party_workspace_bytes(n, k, m) bytes, not overlapping any
+ * other buffer of the call; after the call the wires are at byte offsets hb_party_wire_offset(n, k, m, p).
+ * Inputs and outputs must not overlap each other here (in place is not supported).  wire_bytes (HOST, may
+ * be NULL) receives the bytes each party wrote to its wire.
+ */
+HB_API int hb_relu_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed,
+                         int64_t *out0, int64_t *out1, void *workspace, size_t workspace_bytes,
+                         uint64_t *wire_bytes, void *stream);
+HB_API size_t hb_party_workspace_bytes(size_t n, int k, int m);  /* 0 for an invalid (k, m) or n too large */
+HB_API size_t hb_party_wire_words(size_t n, int k, int m);
+HB_API size_t hb_party_wire_offset(size_t n, int k, int m, int party);
+
+/*
  * Zero-error search for the high cut (Sec. 4.1.2, the "eco" strategy: try every high cut with no low cut
  * and see whether any DReLU result changes).  counts[m - 1] receives the number of elements whose DReLU
  * on the slice [0, m) differs from DReLU on the full ring, for m = 1 .. 64 (counts[63] is always 0).

@@ -12,6 +12,7 @@
 #include "hb_eco.hpp"
 #include "hb_kernels.hpp"
 #include "hb_launch.hpp"
+#include "hb_party.hpp"
 
 namespace {
 
@@ -134,6 +135,30 @@ int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k,
     }
     if (opened_bits) *opened_bits = bits;
     return HB_OK;
+}
+
+// Workspace of the party-faithful path: [wire 0][wire 1][state 0][state 1], every region 256-byte aligned.
+// state p = S, P, G, Z (one word per group each) and D (one word per element).
+struct PartyLayout {
+    uint64_t groups, wire_words, wire_off[2], state_off[2], total_bytes;
+};
+
+PartyLayout party_layout(size_t n, int k, int m)
+{
+    const int w = m - k;
+    const uint64_t L = (64 / w) > 32 ? 32 : (uint64_t)(64 / w);
+    const uint64_t R = (uint64_t)rounds_of(w);
+    PartyLayout lay = {};
+    lay.groups = ((uint64_t)n + L - 1) / L;
+    lay.wire_words = 2 * lay.groups + 4 * lay.groups * R + ((uint64_t)n + 63) / 64 + 2 * (uint64_t)n;
+    auto up = [](uint64_t b) { return (b + 255) & ~255ull; };
+    const uint64_t wire_bytes = up(8 * lay.wire_words), state_bytes = up(8 * (4 * lay.groups + (uint64_t)n));
+    lay.wire_off[0] = 0;
+    lay.wire_off[1] = wire_bytes;
+    lay.state_off[0] = 2 * wire_bytes;
+    lay.state_off[1] = 2 * wire_bytes + state_bytes;
+    lay.total_bytes = 2 * wire_bytes + 2 * state_bytes;
+    return lay;
 }
 
 int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
@@ -270,6 +295,108 @@ int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits,
 int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
 {
     return run_batch(hb::kDrelu, tensors, count, opened_bits, stream);
+}
+
+size_t hb_party_wire_words(size_t n, int k, int m)
+{
+    if (!valid_slice(k, m) || n > HB_MAX_ELEMENTS) return 0;
+    const PartyLayout lay = party_layout(n, k, m);
+    return (size_t)lay.wire_words;
+}
+
+size_t hb_party_workspace_bytes(size_t n, int k, int m)
+{
+    if (!valid_slice(k, m) || n > HB_MAX_ELEMENTS) return 0;
+    return (size_t)party_layout(n, k, m).total_bytes;
+}
+
+size_t hb_party_wire_offset(size_t n, int k, int m, int party)
+{
+    if (!valid_slice(k, m) || n > HB_MAX_ELEMENTS || party < 0 || party > 1) return 0;
+    return (size_t)party_layout(n, k, m).wire_off[party];
+}
+
+int hb_relu_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
+                  int64_t *out1, void *workspace, size_t workspace_bytes, uint64_t *wire_bytes, void *stream)
+{
+    int st = validate_tensor(share0, share1, n, k, m, out0, out1);
+    if (st != HB_OK) return st;
+    const PartyLayout lay = party_layout(n, k, m);
+    if (n > 0) {
+        if (workspace == nullptr || workspace_bytes < lay.total_bytes) return HB_EINVAL;
+        if (((uintptr_t)workspace & 255u) != 0) return HB_EALIGN;
+        st = check_device_buffer(workspace, (lay.total_bytes + 7) / 8);
+        if (st != HB_OK) return st;
+        const Range ws{(uintptr_t)workspace, (uintptr_t)workspace + lay.total_bytes};
+        const Range bufs[4] = {range_of(share0, n), range_of(share1, n), range_of(out0, n), range_of(out1, n)};
+        for (const Range &b : bufs) {
+            if (!disjoint(ws, b)) return HB_EINVAL;
+        }
+        // each party re-reads its share after the other party's kernels have run: no in-place operation here
+        if (!disjoint(bufs[2], bufs[0]) || !disjoint(bufs[2], bufs[1]) || !disjoint(bufs[3], bufs[0]) ||
+            !disjoint(bufs[3], bufs[1]))
+            return HB_EINVAL;
+    }
+    if (wire_bytes) *wire_bytes = 8 * lay.wire_words;
+    if (n == 0) return HB_OK;
+
+    const int w = m - k;
+    hb::PartyShape s = {};
+    s.w = w;
+    s.R = rounds_of(w);
+    s.L = (64 / w) > 32 ? 32 : 64 / w;
+    s.k = k;
+    s.words_per_group = (uint64_t)(5 * (1 + 2 * s.R) + 1);
+    s.field = (w == 64) ? ~0ull : ((1ull << w) - 1);
+    auto repeat = [&](uint64_t f) {
+        uint64_t r = 0;
+        for (int j = 0; j < s.L; ++j) r |= f << (j * w);
+        return r;
+    };
+    s.ones = repeat(1);
+    s.live = repeat(s.field);
+    for (int r = 0; r < 6; ++r) {
+        const int sh = 1 << r;
+        s.keep[r] = (sh >= w) ? 0 : repeat((s.field << sh) & s.field);
+    }
+    s.keep1 = (1 >= w) ? 0 : repeat((s.field << 1) & s.field);
+
+    hb::PartyCtx c = {};
+    char *base = (char *)workspace;
+    c.x[0] = (const uint64_t *)share0;
+    c.x[1] = (const uint64_t *)share1;
+    c.out[0] = (uint64_t *)out0;
+    c.out[1] = (uint64_t *)out1;
+    c.n = n;
+    c.groups = lay.groups;
+    c.seedB = hb::stream_word(seed, 0);
+    c.seedA = hb::stream_word(seed, 1);
+    for (int p = 0; p < 2; ++p) {
+        c.wire[p] = (uint64_t *)(base + lay.wire_off[p]);
+        uint64_t *state = (uint64_t *)(base + lay.state_off[p]);
+        c.S[p] = state;
+        c.P[p] = state + lay.groups;
+        c.G[p] = state + 2 * lay.groups;
+        c.Z[p] = state + 3 * lay.groups;
+        c.D[p] = state + 4 * lay.groups;
+    }
+    c.off_b2a = 2 * lay.groups + 4 * lay.groups * (uint64_t)s.R;
+    c.off_mul = c.off_b2a + (n + 63) / 64;
+
+    auto grid_for = [](uint64_t threads) { return dim3((unsigned)((threads + hb::kPartyBlock - 1) / hb::kPartyBlock), 2); };
+    if ((lay.groups + hb::kPartyBlock - 1) / hb::kPartyBlock > 0x7fffffffull || (n + hb::kPartyBlock - 1) / hb::kPartyBlock > 0x7fffffffull)
+        return HB_EINVAL;
+    hipStream_t q = (hipStream_t)stream;
+    const dim3 blk(hb::kPartyBlock);
+    hipLaunchKernelGGL(hb::party_slice_kernel, grid_for(lay.groups), blk, 0, q, c, s);
+    for (int r = 0; r < s.R; ++r) hipLaunchKernelGGL(hb::party_round_kernel, grid_for(lay.groups), blk, 0, q, c, s, r);
+    hipLaunchKernelGGL(hb::party_sign_kernel, grid_for(lay.groups), blk, 0, q, c, s);
+    hipLaunchKernelGGL(hb::party_b2a_kernel, grid_for((n + 63) / 64), blk, 0, q, c, s);
+    hipLaunchKernelGGL(hb::party_mul_send_kernel, grid_for(n), blk, 0, q, c, s);
+    hipLaunchKernelGGL(hb::party_mul_finish_kernel, grid_for(n), blk, 0, q, c, s);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return HB_OK;
 }
 
 int hb_eco_scan(const int64_t *share0, const int64_t *share1, size_t n, uint64_t *counts, void *stream)

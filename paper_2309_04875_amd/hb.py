@@ -14,6 +14,7 @@ HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP = 0, -1, -2, -3
 BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accounting
 
 EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_eco_scan", "hb_eco_choose",
+           "hb_relu_party", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
            "hb_tensor_seed",
            "hb_opened_bits", "hb_strerror", "hb_last_hip_error")
 
@@ -52,6 +53,14 @@ def load():
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [ctypes.POINTER(hb_tensor), sz, u64p, vp]
+    lib.hb_relu_party.restype = ci
+    lib.hb_relu_party.argtypes = [vp, vp, sz, ci, ci, u64, vp, vp, vp, sz, u64p, vp]
+    lib.hb_party_workspace_bytes.restype = sz
+    lib.hb_party_workspace_bytes.argtypes = [sz, ci, ci]
+    lib.hb_party_wire_words.restype = sz
+    lib.hb_party_wire_words.argtypes = [sz, ci, ci]
+    lib.hb_party_wire_offset.restype = sz
+    lib.hb_party_wire_offset.argtypes = [sz, ci, ci, ci]
     lib.hb_eco_scan.restype = ci
     lib.hb_eco_scan.argtypes = [vp, vp, sz, vp, vp]
     lib.hb_eco_choose.restype = ci
@@ -159,6 +168,45 @@ def hb_relu_batch(batch, stream=None):
 
 def hb_drelu_batch(batch, stream=None):
     return _batch_call("hb_drelu_batch", batch, stream)
+
+
+def hb_party_workspace_bytes(n, k, m):
+    return int(load().hb_party_workspace_bytes(int(n), int(k), int(m)))
+
+
+def hb_party_wire_words(n, k, m):
+    return int(load().hb_party_wire_words(int(n), int(k), int(m)))
+
+
+def hb_party_wire_offset(n, k, m, party):
+    return int(load().hb_party_wire_offset(int(n), int(k), int(m), int(party)))
+
+
+def hb_relu_party(share0, share1, k, m, seed, out0=None, out1=None, workspace=None, stream=None):
+    """Party-faithful ReLU; returns (out0, out1, wire0, wire1, wire_bytes) where wire_p is an int64 view of
+    party p's wire inside the workspace (a uint8 CUDA tensor, allocated here unless one is passed)."""
+    import torch
+    if out0 is None:
+        out0 = torch.empty_like(share0)
+    if out1 is None:
+        out1 = torch.empty_like(share1)
+    n = _tensor_args(share0, share1, out0, out1)
+    need = hb_party_workspace_bytes(n, k, m)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=share0.device)
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous uint8 CUDA tensor")
+    wire_bytes = ctypes.c_uint64(0)
+    st = load().hb_relu_party(share0.data_ptr(), share1.data_ptr(), n, int(k), int(m), int(seed) & (2**64 - 1),
+                              out0.data_ptr(), out1.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                              ctypes.byref(wire_bytes), _stream_handle(stream))
+    _check(st)
+    words = hb_party_wire_words(n, k, m)
+    wires = []
+    for p in (0, 1):
+        off = hb_party_wire_offset(n, k, m, p)
+        wires.append(workspace[off:off + 8 * words].view(torch.int64))
+    return out0, out1, wires[0], wires[1], int(wire_bytes.value)
 
 
 def hb_eco_scan(share0, share1, counts=None, stream=None):
