@@ -34,6 +34,24 @@ VALU_INSTS_PER_WAVE = 2193.0
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9      # CUs x SIMDs x lanes per clock x 2.4 GHz = 39.3e12 32-bit lane-ops/s
 
 
+def party_path_bytes(n, k, m):
+    """Bytes the party-faithful path must move for one ReLU: what each of its kernels reads and writes once
+    (shares, per-group state words, wire words, per-element DReLU shares, results), both parties."""
+    w = m - k
+    L = min(64 // w, 32)
+    R = 0 if w == 1 else (w - 1).bit_length()
+    G = (n + L - 1) // L
+    b2a = (n + 63) // 64
+    words = 2 * n + 2 * G * (2 + 2)                                   # slice: read shares; write S, P, two wire words
+    for r in range(R):                                               # round: read state + both wires' previous message;
+        words += 2 * G * ((1 + 4 if r == 0 else 2 + 8) + 2 + 4)      #        write G, P and four wire words
+    words += 2 * G * (2 + (4 if R else 4) + 1)                       # sign: read S, G, the last G-update opening; write Z
+    words += 2 * (G + b2a)                                           # B2A: read Z, write packed bits
+    words += 2 * (n + 2 * b2a + n + 2 * n)                           # multiply send: read share, B2A words; write D, 2 wire words
+    words += 2 * (4 * n + n)                                         # result: read both wires' multiply words, write result
+    return 8 * words
+
+
 def _time_launches(fn, reps, torch):
     """Average duration in ms of `fn` (one launch) over `reps` launches, by events on the current stream."""
     for _ in range(max(1, reps // 2)):      # same load beforehand, so the clocks have settled
@@ -127,6 +145,13 @@ def main():
         extra["drelu_w8_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         ms = _time_launches(lambda: hb.hb_open(s0, s1, False, out=o0), 300, torch)
         extra["open_copy_ceiling_gbs"] = 24 * spec0.n / (ms * 1e-3) / 1e9
+        ws = torch.empty(hb.hb_party_workspace_bytes(spec0.n, k, m), dtype=torch.uint8, device=dev)
+        ms = _time_launches(lambda: hb.hb_relu_party(s0, s1, k, m, seed0, o0, o1, ws), 40, torch)
+        extra["relu_party_w8_elems_per_s"] = spec0.n / (ms * 1e-3)
+        extra["relu_party_w8_bytes_per_element"] = party_path_bytes(spec0.n, k, m) / spec0.n
+        extra["relu_party_w8_hbm_frac"] = party_path_bytes(spec0.n, k, m) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+        extra["relu_party_w8_wire_bytes_per_element_per_party"] = 8 * hb.hb_party_wire_words(spec0.n, k, m) / spec0.n
+        del ws
         counts = torch.empty(64, dtype=torch.int64, device=dev)
         ms = _time_launches(lambda: hb.hb_eco_scan(s0, s1, counts), 300, torch)
         extra["eco_scan_elems_per_s"] = spec0.n / (ms * 1e-3)
