@@ -152,6 +152,11 @@ def main():
         extra["relu_party_w8_hbm_frac"] = party_path_bytes(spec0.n, k, m) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         extra["relu_party_w8_wire_bytes_per_element_per_party"] = 8 * hb.hb_party_wire_words(spec0.n, k, m) / spec0.n
         del ws
+        xf = torch.randn(spec0.n, device=dev, dtype=torch.float32)
+        yf = torch.empty_like(xf)
+        ms = _time_launches(lambda: hb.hb_sim_relu_f32(xf, k, m, seed0, 1, yf), 100, torch)
+        extra["sim_relu_f32_w8_elems_per_s"] = spec0.n / (ms * 1e-3)       # 8 B per element; bound by VALU like hb_relu
+        del xf, yf
         counts = torch.empty(64, dtype=torch.int64, device=dev)
         ms = _time_launches(lambda: hb.hb_eco_scan(s0, s1, counts), 300, torch)
         extra["eco_scan_elems_per_s"] = spec0.n / (ms * 1e-3)

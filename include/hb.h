@@ -46,7 +46,8 @@ enum hb_status {
     HB_OK = 0,
     HB_EINVAL = -1, /* null pointer with n > 0, bad (k, m), n too large, forbidden overlap, not device memory */
     HB_EALIGN = -2, /* a pointer is not 8-byte aligned */
-    HB_EHIP = -3    /* the HIP runtime refused the launch; hb_last_hip_error() names the reason */
+    HB_EHIP = -3,   /* the HIP runtime refused the launch; hb_last_hip_error() names the reason */
+    HB_ENOTSUP = -4 /* this entry point has no kernel for the requested slice width */
 };
 
 /* Largest n accepted by one call (2^40 elements). */
@@ -132,6 +133,23 @@ HB_API int hb_relu_party(const int64_t *share0, const int64_t *share1, size_t n,
 HB_API size_t hb_party_workspace_bytes(size_t n, int k, int m);  /* 0 for an invalid (k, m) or n too large */
 HB_API size_t hb_party_wire_words(size_t n, int k, int m);
 HB_API size_t hb_party_wire_offset(size_t n, int k, int m, int party);
+
+/*
+ * Float boundary of the single-node simulator (Sec. 4.1.1: floating-point activations are converted to ring
+ * elements, shared, and the ReLU layer is evaluated by the protocol).  Fixed point is x = round(2^16 x_f), ties
+ * to even (Sec. 2.2, Sec. 3.1); NaN encodes as 0 and |2^16 x_f| is clamped to 2^62.
+ *   hb_share_f32 : share0[i] = output i of the SplitMix64 stream started at share_seed (uniform on Z_2^64),
+ *                  share1[i] = round(2^16 x[i]) - share0[i].
+ *   hb_reveal_f32: y[i] = (float)((share0[i] + share1[i] mod 2^64, read as signed) / 2^16).
+ *   hb_sim_relu_f32: y = hb_reveal_f32(hb_relu(hb_share_f32(x, share_seed), k, m, seed)) in ONE kernel that
+ *                  reads 4 bytes and writes 4 bytes per element; bit-identical to the composition.  Only slice
+ *                  widths 4 <= m - k <= 32 have this kernel (HB_ENOTSUP otherwise); y may be x itself.
+ * x, y: device float arrays (4-byte aligned; 8-byte aligned for hb_sim_relu_f32).
+ */
+HB_API int hb_share_f32(const float *x, size_t n, uint64_t share_seed, int64_t *share0, int64_t *share1, void *stream);
+HB_API int hb_reveal_f32(const int64_t *share0, const int64_t *share1, size_t n, float *y, void *stream);
+HB_API int hb_sim_relu_f32(const float *x, size_t n, int k, int m, uint64_t seed, uint64_t share_seed, float *y,
+                           void *stream);
 
 /*
  * Zero-error search for the high cut (Sec. 4.1.2, the "eco" strategy: try every high cut with no low cut

@@ -53,6 +53,11 @@ def lib():
         L.hb_ref_wire_words.argtypes = [_u64, _int, _int]
         L.hb_ref_relu_wire.restype = _int
         L.hb_ref_relu_wire.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _u64p, _u64p]
+        _f32p = ctypes.POINTER(ctypes.c_float)
+        L.hb_ref_share_f32.restype = _int
+        L.hb_ref_share_f32.argtypes = [_f32p, _u64, _u64, _i64p, _i64p]
+        L.hb_ref_reveal_f32.restype = _int
+        L.hb_ref_reveal_f32.argtypes = [_i64p, _i64p, _u64, _f32p]
         L.hb_ref_open.restype = _int
         L.hb_ref_open.argtypes = [_i64p, _i64p, _u64, _int, _int, _i64p]
         _lib = L
@@ -202,3 +207,31 @@ def relu_wire(share0, share1, k, m, seed):
     if st != 0:
         raise ValueError("oracle rejected arguments (status %d)" % st)
     return w0, w1
+
+
+def share_f32(x, share_seed):
+    """Encode float32 to 2^16 fixed point and share: share0 = generator outputs, share1 = x_fixed - share0."""
+    xf = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    s0 = np.empty(xf.size, dtype=np.int64)
+    s1 = np.empty(xf.size, dtype=np.int64)
+    st = lib().hb_ref_share_f32(xf.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), _u64(xf.size),
+                                _u64(share_seed & (2**64 - 1)), _ptr(s0), _ptr(s1))
+    if st != 0:
+        raise ValueError("oracle rejected arguments (status %d)" % st)
+    return s0, s1
+
+
+def reveal_f32(share0, share1):
+    s0, s1 = _as_i64(share0), _as_i64(share1)
+    y = np.empty(s0.size, dtype=np.float32)
+    st = lib().hb_ref_reveal_f32(_ptr(s0), _ptr(s1), _u64(s0.size), y.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if st != 0:
+        raise ValueError("oracle rejected arguments (status %d)" % st)
+    return y
+
+
+def sim_relu_f32(x, k, m, seed, share_seed, threads=1):
+    """The simulator layer: share the floats, run the ReLU protocol, reveal."""
+    s0, s1 = share_f32(x, share_seed)
+    r0, r1, _ = relu(s0, s1, k, m, seed, threads=threads)
+    return reveal_f32(r0, r1)

@@ -15,7 +15,7 @@ def build(force: bool = True) -> str:
     if not force and os.path.exists(LIBRARY) and os.path.getmtime(LIBRARY) >= os.path.getmtime(SOURCE):
         return LIBRARY
     tmp = LIBRARY + ".tmp.%d" % os.getpid()
-    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", SOURCE, "-o", tmp]
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", SOURCE, "-o", tmp, "-lm"]
     subprocess.run(cmd, check=True)
     os.replace(tmp, LIBRARY)
     return LIBRARY

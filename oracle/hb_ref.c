@@ -33,6 +33,7 @@
  * Everything is integer; ring_bits (N) selects the arithmetic ring Z_2^N,
  * 1 <= N <= 64.  N = 64 is the production ring, N = 8 is used for brute force.
  */
+#include <math.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -424,5 +425,44 @@ int hb_ref_relu_wire(const int64_t *share0, const int64_t *share1, uint64_t n, i
             wire[p][off_mul + 2 * i + 1] = t.send_del[p];
         }
     }
+    return HB_REF_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Float boundary of the simulator (Sec. 4.1.1; fixed point of          */
+/* Sec. 2.2 / Sec. 3.1: x = round(2^16 x_f), ties to even).  NaN        */
+/* encodes as 0; |2^16 x_f| is clamped to 2^62.                         */
+/* ------------------------------------------------------------------ */
+int64_t hb_ref_encode_f32(float v)
+{
+    double d = (double)v * 65536.0;
+    if (isnan(d)) d = 0.0;
+    if (d > 4611686018427387904.0) d = 4611686018427387904.0;
+    if (d < -4611686018427387904.0) d = -4611686018427387904.0;
+    return (int64_t)llrint(d);          /* default rounding mode: to nearest, ties to even */
+}
+
+float hb_ref_decode_f32(int64_t v)
+{
+    return (float)((double)v / 65536.0);
+}
+
+int hb_ref_share_f32(const float *x, uint64_t n, uint64_t share_seed, int64_t *share0, int64_t *share1)
+{
+    uint64_t i, state = share_seed;
+    if (n > 0 && (!x || !share0 || !share1)) return HB_REF_EINVAL;
+    for (i = 0; i < n; i++) {
+        const uint64_t r = hb_ref_sm_next(&state);           /* step the generator: output i */
+        share0[i] = (int64_t)r;
+        share1[i] = (int64_t)((uint64_t)hb_ref_encode_f32(x[i]) - r);
+    }
+    return HB_REF_OK;
+}
+
+int hb_ref_reveal_f32(const int64_t *share0, const int64_t *share1, uint64_t n, float *y)
+{
+    uint64_t i;
+    if (n > 0 && (!share0 || !share1 || !y)) return HB_REF_EINVAL;
+    for (i = 0; i < n; i++) y[i] = hb_ref_decode_f32((int64_t)((uint64_t)share0[i] + (uint64_t)share1[i]));
     return HB_REF_OK;
 }

@@ -10,6 +10,7 @@
 #include <utility>
 
 #include "hb_eco.hpp"
+#include "hb_float.hpp"
 #include "hb_kernels.hpp"
 #include "hb_launch.hpp"
 #include "hb_party.hpp"
@@ -39,7 +40,11 @@ bool same(Range a, Range b) { return a.lo == b.lo; }
 bool disjoint(Range a, Range b) { return a.hi <= b.lo || b.hi <= a.lo; }
 
 // The buffer must be memory the GPU can address, and [p, p + 8n) must lie inside one allocation.
-int check_device_buffer(const void *p, size_t n)
+int check_device_bytes(const void *p, size_t bytes);
+
+int check_device_buffer(const void *p, size_t n) { return check_device_bytes(p, n * sizeof(int64_t)); }
+
+int check_device_bytes(const void *p, size_t bytes)
 {
     hipPointerAttribute_t attr;
     hipError_t e = hipPointerGetAttributes(&attr, p);
@@ -65,7 +70,7 @@ int check_device_buffer(const void *p, size_t n)
         return HB_OK;  // allocation kinds without a queryable range: the attribute check has passed
     }
     const uintptr_t lo = (uintptr_t)base, hi = lo + size;
-    const Range r = range_of(p, n);
+    const Range r{(uintptr_t)p, (uintptr_t)p + bytes};
     return (r.lo >= lo && r.hi <= hi) ? HB_OK : HB_EINVAL;
 }
 
@@ -84,6 +89,14 @@ int check_common(const void *const *ptrs, int count, size_t n)
         if (st != HB_OK) return st;
     }
     return HB_OK;
+}
+
+// A device buffer of n floats with the given alignment.
+int check_float_buffer(const void *p, size_t n, unsigned align)
+{
+    if (p == nullptr) return HB_EINVAL;
+    if (((uintptr_t)p & (align - 1)) != 0) return HB_EALIGN;
+    return check_device_bytes(p, n * sizeof(float));
 }
 
 bool all_aligned16(const void *const *ptrs, int count)
@@ -399,6 +412,60 @@ int hb_relu_party(const int64_t *share0, const int64_t *share1, size_t n, int k,
     return HB_OK;
 }
 
+int hb_share_f32(const float *x, size_t n, uint64_t share_seed, int64_t *share0, int64_t *share1, void *stream)
+{
+    const void *ptrs[2] = {share0, share1};
+    int st = check_common(ptrs, 2, n);
+    if (st != HB_OK) return st;
+    if (n == 0) return HB_OK;
+    st = check_float_buffer(x, n, 4);
+    if (st != HB_OK) return st;
+    const Range rx{(uintptr_t)x, (uintptr_t)x + 4 * n}, r0 = range_of(share0, n), r1 = range_of(share1, n);
+    if (!disjoint(r0, r1) || !disjoint(rx, r0) || !disjoint(rx, r1)) return HB_EINVAL;
+    const uint64_t blocks = ((uint64_t)n + hb::kBlock - 1) / hb::kBlock;
+    if (blocks > 0x7fffffffull) return HB_EINVAL;
+    hipLaunchKernelGGL(hb::share_f32_kernel, dim3((unsigned)blocks), dim3(hb::kBlock), 0, (hipStream_t)stream, x,
+                       (uint64_t)n, share_seed, (uint64_t *)share0, (uint64_t *)share1);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HB_OK : fail_hip(e, "kernel launch");
+}
+
+int hb_reveal_f32(const int64_t *share0, const int64_t *share1, size_t n, float *y, void *stream)
+{
+    const void *ptrs[2] = {share0, share1};
+    int st = check_common(ptrs, 2, n);
+    if (st != HB_OK) return st;
+    if (n == 0) return HB_OK;
+    st = check_float_buffer(y, n, 4);
+    if (st != HB_OK) return st;
+    const Range ry{(uintptr_t)y, (uintptr_t)y + 4 * n};
+    if (!disjoint(ry, range_of(share0, n)) || !disjoint(ry, range_of(share1, n))) return HB_EINVAL;
+    const uint64_t blocks = ((uint64_t)n + hb::kBlock - 1) / hb::kBlock;
+    if (blocks > 0x7fffffffull) return HB_EINVAL;
+    hipLaunchKernelGGL(hb::reveal_f32_kernel, dim3((unsigned)blocks), dim3(hb::kBlock), 0, (hipStream_t)stream,
+                       (const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, y);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HB_OK : fail_hip(e, "kernel launch");
+}
+
+int hb_sim_relu_f32(const float *x, size_t n, int k, int m, uint64_t seed, uint64_t share_seed, float *y, void *stream)
+{
+    if (!valid_slice(k, m)) return HB_EINVAL;
+    if (n > HB_MAX_ELEMENTS) return HB_EINVAL;
+    const hb::SimLauncher f = hb::launcher_table().sim[m - k - 1];
+    if (f == nullptr) return HB_ENOTSUP;
+    if (n == 0) return HB_OK;
+    int st = check_float_buffer(x, n, 8);
+    if (st != HB_OK) return st;
+    st = check_float_buffer(y, n, 8);
+    if (st != HB_OK) return st;
+    const Range rx{(uintptr_t)x, (uintptr_t)x + 4 * n}, ry{(uintptr_t)y, (uintptr_t)y + 4 * n};
+    if (!(rx.lo == ry.lo || disjoint(rx, ry))) return HB_EINVAL;
+    const hipError_t e = f(x, (uint64_t)n, k, hb::stream_word(seed, 0), hb::stream_word(seed, 1), share_seed, y,
+                           (hipStream_t)stream);
+    return e == hipSuccess ? HB_OK : fail_hip(e, "kernel launch");
+}
+
 int hb_eco_scan(const int64_t *share0, const int64_t *share1, size_t n, uint64_t *counts, void *stream)
 {
     if (counts == nullptr) return HB_EINVAL;
@@ -493,6 +560,7 @@ const char *hb_strerror(int status)
     case HB_EINVAL: return "invalid argument (null pointer, bad (k, m), size, overlap, or not device memory)";
     case HB_EALIGN: return "pointer is not 8-byte aligned";
     case HB_EHIP: return "HIP runtime error (see hb_last_hip_error)";
+    case HB_ENOTSUP: return "no kernel for this slice width in this entry point";
     default: return "unknown status";
     }
 }

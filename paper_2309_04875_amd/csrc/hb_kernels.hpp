@@ -177,11 +177,95 @@ struct TileTraits {
     static constexpr int kSliceBytes = kPacked ? 2 * kWave * 8 : kTile * (int)sizeof(Entry);
 };
 
+// ---- where a tile's element pairs come from and where the results go ----------------------------------------
+// Shares in, shares out: the library's normal boundary.
+struct ShareIO {
+    const uint64_t *x0, *x1;
+    uint64_t *o0, *o1;
+    __device__ __forceinline__ void load_pair(uint64_t i, uint64_t n, U64x2 &a, U64x2 &b) const
+    {
+        if (i + 1 < n) {
+            a = *reinterpret_cast<const U64x2 *>(x0 + i);
+            b = *reinterpret_cast<const U64x2 *>(x1 + i);
+        } else if (i < n) {
+            a.a = x0[i];
+            b.a = x1[i];
+        }
+    }
+    __device__ __forceinline__ void store_pair(uint64_t i, uint64_t n, Pair r0, Pair r1) const
+    {
+        if (i + 1 < n) {
+            *reinterpret_cast<U64x2 *>(o0 + i) = U64x2{r0.p0, r1.p0};
+            *reinterpret_cast<U64x2 *>(o1 + i) = U64x2{r0.p1, r1.p1};
+        } else if (i < n) {
+            o0[i] = r0.p0;
+            o1[i] = r0.p1;
+        }
+    }
+};
+
+// Fixed point of the paper's setting (Sec. 2.2 "Operation of CrypTen", Sec. 3.1): x = round(2^16 x_f),
+// ties to even; NaN encodes as 0 and magnitudes are clamped to 2^62 so the conversion is defined for every float.
+__host__ __device__ __forceinline__ uint64_t encode_fixed16(float v)
+{
+    double d = (double)v * 65536.0;
+    if (!(d == d)) d = 0.0;
+    d = d > 0x1p62 ? 0x1p62 : (d < -0x1p62 ? -0x1p62 : d);
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (uint64_t)__double2ll_rn(d);
+#else
+    return (uint64_t)(long long)__builtin_rint(d);
+#endif
+}
+
+__host__ __device__ __forceinline__ float decode_fixed16(uint64_t v)
+{
+    return (float)((double)(int64_t)v * (1.0 / 65536.0));
+}
+
+struct alignas(8) F32x2 {
+    float a, b;
+};
+
+// Plaintext floats in, plaintext floats out (the single-node simulator of Sec. 4.1.1): the load encodes to fixed
+// point and shares additively with share0[i] = output i of the SplitMix64 stream started at seedS; the store opens
+// the two result shares and decodes.  Nothing but 4 bytes per element travels each way.
+struct FloatIO {
+    const float *x;
+    float *y;
+    uint64_t seedS;
+    __device__ __forceinline__ void load_pair(uint64_t i, uint64_t n, U64x2 &a, U64x2 &b) const
+    {
+        float f0 = 0.0f, f1 = 0.0f;
+        if (i + 1 < n) {
+            const F32x2 v = *reinterpret_cast<const F32x2 *>(x + i);
+            f0 = v.a;
+            f1 = v.b;
+        } else if (i < n) {
+            f0 = x[i];
+        } else {
+            return;
+        }
+        const uint64_t z = seedS + (i + 1) * kGamma;
+        a.a = mix64(z);
+        a.b = mix64(z + kGamma);
+        b.a = encode_fixed16(f0) - a.a;
+        b.b = encode_fixed16(f1) - a.b;
+    }
+    __device__ __forceinline__ void store_pair(uint64_t i, uint64_t n, Pair r0, Pair r1) const
+    {
+        if (i + 1 < n) {
+            *reinterpret_cast<F32x2 *>(y + i) = F32x2{decode_fixed16(r0.p0 + r0.p1), decode_fixed16(r1.p0 + r1.p1)};
+        } else if (i < n) {
+            y[i] = decode_fixed16(r0.p0 + r0.p1);
+        }
+    }
+};
+
 // Work of one wavefront on wave-tile `tile` of one tensor.  slice_lds / verdict: this wave's LDS.
-template <int W, int MODE>
-__device__ __forceinline__ void tile_body(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t seedB,
-                                          uint64_t seedA, uint64_t *o0, uint64_t *o1, uint64_t tile, int lane,
-                                          unsigned char *slice_lds, U64x2 *verdict)
+template <int W, int MODE, class IO>
+__device__ __forceinline__ void tile_body(const IO &io, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
+                                          uint64_t tile, int lane, unsigned char *slice_lds, U64x2 *verdict)
 {
     using T = TileTraits<W>;
     using S = Shape<W>;
@@ -199,13 +283,7 @@ __device__ __forceinline__ void tile_body(const uint64_t *x0, const uint64_t *x1
         xb[c] = U64x2{0, 0};
         if (e < T::kTile) {
             const uint64_t i = tile0 + e;
-            if (i + 1 < n) {
-                xa[c] = *reinterpret_cast<const U64x2 *>(x0 + i);
-                xb[c] = *reinterpret_cast<const U64x2 *>(x1 + i);
-            } else if (i < n) {
-                xa[c].a = x0[i];
-                xb[c].a = x1[i];
-            }
+            io.load_pair(i, n, xa[c], xb[c]);
             if constexpr (T::kPacked) {
                 // the pair's two fields of party 0 / party 1, already at their place relative to the pair
                 using Item = typename T::Item;
@@ -281,13 +359,7 @@ __device__ __forceinline__ void tile_body(const uint64_t *x0, const uint64_t *x1
                     r[h] = (MODE == kDrelu) ? D : beaver_mul(Pair{h ? xa[c].b : xa[c].a, h ? xb[c].b : xb[c].a}, D, zA);
                 }
             }
-            if (i + 1 < n) {
-                *reinterpret_cast<U64x2 *>(o0 + i) = U64x2{r[0].p0, r[1].p0};
-                *reinterpret_cast<U64x2 *>(o1 + i) = U64x2{r[0].p1, r[1].p1};
-            } else if (i < n) {
-                o0[i] = r[0].p0;
-                o1[i] = r[0].p1;
-            }
+            io.store_pair(i, n, r[0], r[1]);
         }
     }
 }
@@ -303,7 +375,7 @@ tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t 
     const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
     const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     if (tile * T::kTile >= n) return;        // whole wavefront beyond the tensor (uniform per wave)
-    tile_body<W, MODE>(x0, x1, n, k, seedB, seedA, o0, o1, tile, lane, slices_all[wv], verdict_all[wv]);
+    tile_body<W, MODE>(ShareIO{x0, x1, o0, o1}, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 // Several tensors of one slice width in a single launch.  The descriptors travel in the kernel
@@ -338,7 +410,21 @@ tile_batch_kernel(const BatchArgs args)
     while (gt >= args.tile_end[ti]) ++ti;                                     // uniform per wave, at most kBatchMax steps
     const uint64_t tile = gt - (ti ? args.tile_end[ti - 1] : 0);
     const BatchTensor &d = args.t[ti];
-    tile_body<W, MODE>(d.x0, d.x1, d.n, d.k, d.seedB, d.seedA, d.o0, d.o1, tile, lane, slices_all[wv], verdict_all[wv]);
+    tile_body<W, MODE>(ShareIO{d.x0, d.x1, d.o0, d.o1}, d.n, d.k, d.seedB, d.seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+}
+
+// The simulator kernel: ReLU on plaintext floats through the whole protocol, 8 bytes of traffic per element.
+template <int W>
+__global__ void __launch_bounds__(kBlock)
+tile_sim_kernel(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t seedS, float *y)
+{
+    using T = TileTraits<W>;
+    __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][T::kSliceBytes];
+    __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];
+    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
+    if (tile * T::kTile >= n) return;
+    tile_body<W, kRelu>(FloatIO{x, y, seedS}, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 }  // namespace hb

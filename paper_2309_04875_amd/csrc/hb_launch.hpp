@@ -16,9 +16,14 @@ using GroupLauncher = hipError_t (*)(const uint64_t *x0, const uint64_t *x1, uin
 // Launches the tensors described by `args` (all of one slice width, tile-kernel eligible) in one grid.
 using BatchLauncher = hipError_t (*)(const BatchArgs &args, hipStream_t stream);
 
+// The float-in / float-out simulator kernel of one slice width.
+using SimLauncher = hipError_t (*)(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t seedS,
+                                   float *y, hipStream_t stream);
+
 struct LauncherTable {
     GroupLauncher f[3][64];       // [mode][w - 1]
     BatchLauncher batch[3][64];   // null where the width has no tile kernel
+    SimLauncher sim[64];          // null where the width has no tile kernel
 };
 
 LauncherTable &launcher_table();

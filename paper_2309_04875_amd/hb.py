@@ -10,11 +10,11 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIBRARY = os.path.join(HERE, "libhb.so")
 
-HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP = 0, -1, -2, -3
+HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP, HB_ENOTSUP = 0, -1, -2, -3, -4
 BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accounting
 
 EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_eco_scan", "hb_eco_choose",
-           "hb_relu_party", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
+           "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
            "hb_tensor_seed",
            "hb_opened_bits", "hb_strerror", "hb_last_hip_error")
 
@@ -53,6 +53,12 @@ def load():
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [ctypes.POINTER(hb_tensor), sz, u64p, vp]
+    lib.hb_share_f32.restype = ci
+    lib.hb_share_f32.argtypes = [vp, sz, u64, vp, vp, vp]
+    lib.hb_reveal_f32.restype = ci
+    lib.hb_reveal_f32.argtypes = [vp, vp, sz, vp, vp]
+    lib.hb_sim_relu_f32.restype = ci
+    lib.hb_sim_relu_f32.argtypes = [vp, sz, ci, ci, u64, u64, vp, vp]
     lib.hb_relu_party.restype = ci
     lib.hb_relu_party.argtypes = [vp, vp, sz, ci, ci, u64, vp, vp, vp, sz, u64p, vp]
     lib.hb_party_workspace_bytes.restype = sz
@@ -168,6 +174,53 @@ def hb_relu_batch(batch, stream=None):
 
 def hb_drelu_batch(batch, stream=None):
     return _batch_call("hb_drelu_batch", batch, stream)
+
+
+def _float_arg(t):
+    import torch
+    if not isinstance(t, torch.Tensor) or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError("expected a contiguous float32 CUDA tensor")
+    return t.numel()
+
+
+def hb_share_f32(x, share_seed, share0=None, share1=None, stream=None):
+    """Encode to 2^16 fixed point and share additively; returns (share0, share1)."""
+    import torch
+    n = _float_arg(x)
+    if share0 is None:
+        share0 = torch.empty(x.shape, dtype=torch.int64, device=x.device)
+    if share1 is None:
+        share1 = torch.empty(x.shape, dtype=torch.int64, device=x.device)
+    if _tensor_args(share0, share1) != n:
+        raise ValueError("tensors differ in size")
+    _check(load().hb_share_f32(x.data_ptr(), n, int(share_seed) & (2**64 - 1), share0.data_ptr(), share1.data_ptr(),
+                               _stream_handle(stream)))
+    return share0, share1
+
+
+def hb_reveal_f32(share0, share1, out=None, stream=None):
+    """Open and decode to float32."""
+    import torch
+    n = _tensor_args(share0, share1)
+    if out is None:
+        out = torch.empty(share0.shape, dtype=torch.float32, device=share0.device)
+    if _float_arg(out) != n:
+        raise ValueError("tensors differ in size")
+    _check(load().hb_reveal_f32(share0.data_ptr(), share1.data_ptr(), n, out.data_ptr(), _stream_handle(stream)))
+    return out
+
+
+def hb_sim_relu_f32(x, k, m, seed, share_seed, out=None, stream=None):
+    """Approximate ReLU of plaintext floats through the protocol, one kernel (widths 4..32 only)."""
+    import torch
+    n = _float_arg(x)
+    if out is None:
+        out = torch.empty_like(x)
+    if _float_arg(out) != n:
+        raise ValueError("tensors differ in size")
+    _check(load().hb_sim_relu_f32(x.data_ptr(), n, int(k), int(m), int(seed) & (2**64 - 1),
+                                  int(share_seed) & (2**64 - 1), out.data_ptr(), _stream_handle(stream)))
+    return out
 
 
 def hb_party_workspace_bytes(n, k, m):

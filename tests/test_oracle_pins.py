@@ -453,3 +453,45 @@ def test_eco_scan_small_ring_brute_force():
     for m in range(1, 9):
         assert counts[m - 1] == int((((xs >> (m - 1)) & 1) != (xs >> 7)).sum())
     assert (counts[8:] == 0).all()
+
+
+# ----------------------------------------------------------------------------------------------
+# float boundary of the simulator (Sec. 4.1.1; fixed point of Sec. 2.2 / Sec. 3.1)
+# ----------------------------------------------------------------------------------------------
+
+def test_float_encode_share_reveal():
+    rng = np.random.default_rng(51)
+    x = np.concatenate([rng.standard_normal(2000).astype(np.float32) * 3,
+                        np.array([0.0, -0.0, 1.5 / 65536, 2.5 / 65536, -1.5 / 65536, -2.5 / 65536, 0.5 / 65536,
+                                  1.0, -1.0, 123.456, 2.0 ** 20, -2.0 ** 30], dtype=np.float32)])
+    s0, s1 = oracle.share_f32(x, 99)
+    # share0 is the generator's output sequence; the shares add up to round-half-even(x * 2^16)
+    assert [int(v) & U64 for v in s0[:50]] == oracle.sm_sequence(99, 50)
+    enc = (s0.view(np.uint64) + s1.view(np.uint64)).view(np.int64)
+    assert np.array_equal(enc, np.rint(x.astype(np.float64) * 65536.0).astype(np.int64))
+    assert [int(v) for v in enc[2002:2007]] == [2, 2, -2, -2, 0]           # ties go to even
+    y = oracle.reveal_f32(s0, s1)
+    assert np.array_equal(y, (enc.astype(np.float64) / 65536.0).astype(np.float32))
+    # special values: NaN encodes as 0, huge magnitudes clamp to +-2^62
+    sp = np.array([np.nan, np.inf, -np.inf, 3e38, -3e38], dtype=np.float32)
+    a, b = oracle.share_f32(sp, 5)
+    assert [int(v) for v in (a.view(np.uint64) + b.view(np.uint64)).view(np.int64)] == [0, 1 << 62, -(1 << 62), 1 << 62, -(1 << 62)]
+
+
+def test_simulated_relu_on_floats():
+    """Full ring: exactly ReLU of the quantised input.  Reduced ring: the same wherever the value sits inside the window,
+    and small positives may be pruned to zero (Theorem 2) but nothing else changes."""
+    rng = np.random.default_rng(52)
+    x = (rng.standard_normal(4000) * 2).astype(np.float32)
+    q = np.rint(x.astype(np.float64) * 65536.0) / 65536.0
+    y = oracle.sim_relu_f32(x, 0, 64, SEED, 1234)
+    assert np.array_equal(y, np.maximum(q, 0).astype(np.float32))
+    k, m = 12, 20
+    y = oracle.sim_relu_f32(x, k, m, SEED, 1234)
+    xi = np.rint(x.astype(np.float64) * 65536.0).astype(np.int64)
+    inside = (np.abs(xi) < (1 << (m - 1)) - (1 << k))
+    big = inside & ((xi >= (1 << k)) | (xi < 0))
+    assert np.array_equal(y[big], np.maximum(q, 0).astype(np.float32)[big])
+    small = inside & (xi >= 0) & (xi < (1 << k))
+    assert np.all((y[small] == 0) | (y[small] == q[small].astype(np.float32)))
+    assert (y[small] == 0).any()
