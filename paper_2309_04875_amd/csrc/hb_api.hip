@@ -53,7 +53,14 @@ int check_device_bytes(const void *p, size_t bytes)
         return HB_EINVAL;  // not known to the HIP runtime: plain host memory or a wild pointer
     }
     switch (attr.type) {
-    case hipMemoryTypeDevice:
+    case hipMemoryTypeDevice: {   // memory of another GPU is not addressable from the kernels launched here
+        int current = -1;
+        if (hipGetDevice(&current) != hipSuccess || attr.device != current) {
+            (void)hipGetLastError();
+            return HB_EINVAL;
+        }
+        break;
+    }
     case hipMemoryTypeManaged:
         break;
     case hipMemoryTypeHost:  // pinned host memory is usable only through its device-side address

@@ -1,9 +1,16 @@
-// Kernels: one thread evaluates one group of L = min(64/W, 32) consecutive elements.
+// Kernels of the fused path: both parties of an element live in one thread and every opening stays in registers.
 //
-// A thread packs the slices of its L elements of both shares into two SWAR words, runs the whole
-// circuit on them in registers (gate 0, all prefix rounds, sign), then finishes its elements one by
-// one (B2A, Beaver multiply) and stores the result shares.  Nothing but the input shares is read from
-// memory and nothing but the output shares is written: the algorithmic traffic is 32 bytes per element.
+//   group_kernel       one thread per group of L = min(64/W, 32) consecutive elements: packs the slices of its
+//                      elements into two SWAR words, runs the circuit (gate 0, all prefix rounds, sign), then
+//                      finishes its elements one by one (B2A, Beaver multiply).  No LDS.  Used for L = 1, L > 16
+//                      and for buffers that are only 8-byte aligned.
+//   tile_kernel        one wavefront per 64 groups, coalesced 16-byte memory traffic per lane, slices and sign
+//   tile_batch_kernel  words exchanged through wave-private LDS (described above the kernel).  The batch form
+//                      serves several tensors of one width; tile_sim_kernel is the float-in / float-out form.
+//   open_kernel        share0 + share1 or share0 ^ share1.
+//
+// Nothing but the input shares is read from memory and nothing but the output shares is written: the algorithmic
+// traffic is 32 bytes per element (24 for open_kernel, 8 for tile_sim_kernel).
 #pragma once
 
 #include <type_traits>
