@@ -35,12 +35,14 @@ def lib():
         L.hb_ref_tensor_seed.argtypes = [_u64, _u64]
         L.hb_ref_opened_bits.restype = _u64
         L.hb_ref_opened_bits.argtypes = [_int, _int, _int, _u64]
+        L.hb_ref_opened_bits_v.restype = _u64
+        L.hb_ref_opened_bits_v.argtypes = [_int, _int, _int, _u64, _int]
         L.hb_ref_and_gate.restype = None
         L.hb_ref_and_gate.argtypes = [_u64] * 10 + [_u64p, _u64p]
-        L.hb_ref_eval_range.restype = _int
-        L.hb_ref_eval_range.argtypes = [_i64p, _i64p, _u64, _u64, _int, _int, _u64, _int, _int, _i64p, _i64p]
-        L.hb_ref_eval_at.restype = _int
-        L.hb_ref_eval_at.argtypes = [_i64p, _i64p, _u64p, _u64, _int, _int, _u64, _int, _int, _i64p, _i64p]
+        L.hb_ref_eval_range_v.restype = _int
+        L.hb_ref_eval_range_v.argtypes = [_i64p, _i64p, _u64, _u64, _int, _int, _u64, _int, _int, _int, _i64p, _i64p]
+        L.hb_ref_eval_at_v.restype = _int
+        L.hb_ref_eval_at_v.argtypes = [_i64p, _i64p, _u64p, _u64, _int, _int, _u64, _int, _int, _int, _i64p, _i64p]
         L.hb_ref_drelu.restype = _int
         L.hb_ref_drelu.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _int, _i64p, _i64p, _u64p]
         L.hb_ref_relu.restype = _int
@@ -95,8 +97,11 @@ def tensor_seed(root_seed, tensor_id):
     return int(lib().hb_ref_tensor_seed(_u64(root_seed & (2**64 - 1)), _u64(tensor_id)))
 
 
-def opened_bits(relu, k, m, n):
-    return int(lib().hb_ref_opened_bits(int(bool(relu)), k, m, _u64(n)))
+VARIANT_PER_GATE, VARIANT_SHARED_MASK = 0, 1
+
+
+def opened_bits(relu, k, m, n, variant=0):
+    return int(lib().hb_ref_opened_bits_v(int(bool(relu)), k, m, _u64(n), variant))
 
 
 def and_gate(U0, U1, V0, V1, a0, a1, b0, b1, c0, mask):
@@ -106,7 +111,7 @@ def and_gate(U0, U1, V0, V1, a0, a1, b0, b1, c0, mask):
     return int(z0.value), int(z1.value)
 
 
-def evaluate(share0, share1, k, m, seed, what, ring_bits=64, first=0, threads=1):
+def evaluate(share0, share1, k, m, seed, what, ring_bits=64, first=0, threads=1, variant=0):
     """Run the protocol on a whole array; returns the two share arrays selected by `what`.
 
     threads > 1 splits the element range into contiguous chunks evaluated by a thread pool
@@ -121,8 +126,9 @@ def evaluate(share0, share1, k, m, seed, what, ring_bits=64, first=0, threads=1)
     L = lib()
 
     def run(lo, hi):
-        st = L.hb_ref_eval_range(_ptr(s0[lo:hi]), _ptr(s1[lo:hi]), _u64(first + lo), _u64(hi - lo), k, m,
-                                 _u64(seed & (2**64 - 1)), ring_bits, what, _ptr(o0[lo:hi]), _ptr(o1[lo:hi]))
+        st = L.hb_ref_eval_range_v(_ptr(s0[lo:hi]), _ptr(s1[lo:hi]), _u64(first + lo), _u64(hi - lo), k, m,
+                                   _u64(seed & (2**64 - 1)), ring_bits, variant, what,
+                                   _ptr(o0[lo:hi]), _ptr(o1[lo:hi]))
         if st != 0:
             raise ValueError("oracle rejected arguments (status %d)" % st)
 
@@ -130,8 +136,8 @@ def evaluate(share0, share1, k, m, seed, what, ring_bits=64, first=0, threads=1)
     if threads == 1 or n < 4096:
         # n == 0 still validates the arguments
         if n == 0:
-            st = L.hb_ref_eval_range(None, None, _u64(first), _u64(0), k, m, _u64(seed & (2**64 - 1)),
-                                     ring_bits, what, None, None)
+            st = L.hb_ref_eval_range_v(None, None, _u64(first), _u64(0), k, m, _u64(seed & (2**64 - 1)),
+                                       ring_bits, variant, what, None, None)
             if st != 0:
                 raise ValueError("oracle rejected arguments (status %d)" % st)
         else:
@@ -143,7 +149,7 @@ def evaluate(share0, share1, k, m, seed, what, ring_bits=64, first=0, threads=1)
     return o0, o1
 
 
-def evaluate_at(share0, share1, index, k, m, seed, what, ring_bits=64):
+def evaluate_at(share0, share1, index, k, m, seed, what, ring_bits=64, variant=0):
     """Scattered elements: element index[i] of the tensor has share values share0[i], share1[i]."""
     s0, s1 = _as_i64(share0), _as_i64(share1)
     idx = np.ascontiguousarray(index, dtype=np.uint64).reshape(-1)
@@ -151,21 +157,21 @@ def evaluate_at(share0, share1, index, k, m, seed, what, ring_bits=64):
         raise ValueError("length mismatch")
     o0 = np.empty(idx.size, dtype=np.int64)
     o1 = np.empty(idx.size, dtype=np.int64)
-    st = lib().hb_ref_eval_at(_ptr(s0), _ptr(s1), _ptr(idx, _u64p), _u64(idx.size), k, m,
-                              _u64(seed & (2**64 - 1)), ring_bits, what, _ptr(o0), _ptr(o1))
+    st = lib().hb_ref_eval_at_v(_ptr(s0), _ptr(s1), _ptr(idx, _u64p), _u64(idx.size), k, m,
+                                _u64(seed & (2**64 - 1)), ring_bits, variant, what, _ptr(o0), _ptr(o1))
     if st != 0:
         raise ValueError("oracle rejected arguments (status %d)" % st)
     return o0, o1
 
 
-def drelu(share0, share1, k, m, seed, ring_bits=64, threads=1):
-    o0, o1 = evaluate(share0, share1, k, m, seed, WHAT_DRELU, ring_bits, threads=threads)
-    return o0, o1, opened_bits(False, k, m, o0.size)
+def drelu(share0, share1, k, m, seed, ring_bits=64, threads=1, variant=0):
+    o0, o1 = evaluate(share0, share1, k, m, seed, WHAT_DRELU, ring_bits, threads=threads, variant=variant)
+    return o0, o1, opened_bits(False, k, m, o0.size, variant)
 
 
-def relu(share0, share1, k, m, seed, ring_bits=64, threads=1):
-    o0, o1 = evaluate(share0, share1, k, m, seed, WHAT_RELU, ring_bits, threads=threads)
-    return o0, o1, opened_bits(True, k, m, o0.size)
+def relu(share0, share1, k, m, seed, ring_bits=64, threads=1, variant=0):
+    o0, o1 = evaluate(share0, share1, k, m, seed, WHAT_RELU, ring_bits, threads=threads, variant=variant)
+    return o0, o1, opened_bits(True, k, m, o0.size, variant)
 
 
 def open_shares(share0, share1, binary=False, ring_bits=64):

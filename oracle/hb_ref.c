@@ -24,6 +24,12 @@
  * (k, m) = (lowest kept bit, one past the highest kept bit), w = m - k, i.e.
  * the paper's x[m:k].
  *
+ * A second dealer layout ("variant 1") is offered beside the standard one: the
+ * two AND gates of a prefix round both have the old propagate word P as first
+ * operand, so one mask a serves both (P ^ a is opened once), and the round
+ * opens 3w bits instead of 4w.  The circuit, and so every reconstructed
+ * quantity, is unchanged; only the dealer words and the shares differ.
+ *
  * Pins: every reconstructed quantity (adder sum, sign, DReLU, ReLU, opened-bit
  * counts, the generator) is pinned by the non-GPU tests against closed forms,
  * brute force on an 8-bit ring, the paper's worked example and published
@@ -85,6 +91,7 @@ typedef struct {
     uint64_t ring;      /* 2^N - 1                                             */
     uint64_t seedB;     /* binary-material stream   B[j] = SM(seedB)[j]        */
     uint64_t seedA;     /* arithmetic-material stream A[j] = SM(seedA)[j]      */
+    int variant;        /* 0: every gate has its own triple; 1: the two gates of a round share the mask of P */
 } shape_t;
 
 static int rounds_for(int w)
@@ -94,8 +101,27 @@ static int rounds_for(int w)
     return R;
 }
 
-static int make_shape(shape_t *s, int k, int m, uint64_t seed, int ring_bits)
+/* Position, inside a group's run of dealer words, of slot (0:a_0 1:a_1 2:b_0 3:b_1 4:c_0) of gate q.
+ * Standard layout: five words per gate.  Shared-mask variant: gate 0 as before; round r owns eight words
+ * a_0 a_1 | b_0 b_1 c_0 of the G-update | b_0 b_1 c_0 of the P-update, the mask a of P serving both gates. */
+static uint64_t word_of(const shape_t *s, int q, int slot)
 {
+    if (!s->variant || q == 0) return 5u * (uint64_t)q + (uint64_t)slot;
+    const int r = (q - 1) / 2, is_p_update = (q - 1) % 2;
+    const uint64_t base = 5u + 8u * (uint64_t)r;
+    if (slot < 2 || !is_p_update) return base + (uint64_t)slot;
+    return base + 3u + (uint64_t)slot;
+}
+
+static uint64_t b2a_word_of(const shape_t *s)
+{
+    return s->variant ? 5u + 8u * (uint64_t)s->R : 5u * (uint64_t)(1 + 2 * s->R);
+}
+
+static int make_shape_v(shape_t *s, int k, int m, uint64_t seed, int ring_bits, int variant)
+{
+    if (variant != 0 && variant != 1) return HB_REF_EINVAL;
+    s->variant = variant;
     if (ring_bits < 1 || ring_bits > 64) return HB_REF_EINVAL;
     if (k < 0 || m <= k || m > ring_bits) return HB_REF_EINVAL;
     s->k = k;
@@ -104,7 +130,7 @@ static int make_shape(shape_t *s, int k, int m, uint64_t seed, int ring_bits)
     s->R = rounds_for(s->w);
     s->L = 64 / s->w;
     if (s->L > 32) s->L = 32;
-    s->Wg = (uint64_t)(5 * (1 + 2 * s->R) + 1);
+    s->Wg = b2a_word_of(s) + 1;
     s->mask = (s->w == 64) ? ~0ULL : ((1ULL << s->w) - 1);
     s->ring = (ring_bits == 64) ? ~0ULL : ((1ULL << ring_bits) - 1);
     s->seedB = hb_ref_sm(seed, 0);
@@ -112,17 +138,29 @@ static int make_shape(shape_t *s, int k, int m, uint64_t seed, int ring_bits)
     return HB_REF_OK;
 }
 
+static int make_shape(shape_t *s, int k, int m, uint64_t seed, int ring_bits)
+{
+    return make_shape_v(s, k, m, seed, ring_bits, 0);
+}
+
 /* Opened (publicly reconstructed) bits: gate 0 opens 2w, every prefix round
  * opens 4w (two AND gates), B2A opens 1, the multiply opens two ring elements
- * (counted as 128 on the 64-bit production ring). */
-uint64_t hb_ref_opened_bits(int relu, int k, int m, uint64_t n)
+ * (counted as 128 on the 64-bit production ring).
+ * Variant 1: a prefix round opens P ^ a once, for both gates, and the two
+ * second operands: 3w bits instead of 4w. */
+uint64_t hb_ref_opened_bits_v(int relu, int k, int m, uint64_t n, int variant)
 {
     if (k < 0 || m <= k || m > 64) return 0;
     uint64_t w = (uint64_t)(m - k);
     uint64_t R = (uint64_t)rounds_for((int)w);
-    uint64_t per = 2 * w * (1 + 2 * R) + 1;
+    uint64_t per = (variant ? 2 * w + 3 * w * R : 2 * w * (1 + 2 * R)) + 1;
     if (relu) per += 128;
     return n * per;
+}
+
+uint64_t hb_ref_opened_bits(int relu, int k, int m, uint64_t n)
+{
+    return hb_ref_opened_bits_v(relu, k, m, n, 0);
 }
 
 /* ------------------------------------------------------------------ */
@@ -185,7 +223,7 @@ static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
         S[p] = P[p];
     }
 
-#define FIELD(q, slot) ((hb_ref_sm(s->seedB, base + 5u * (uint64_t)(q) + (slot)) >> fsh) & mask)
+#define FIELD(q, slot) ((hb_ref_sm(s->seedB, base + word_of(s, (q), (slot))) >> fsh) & mask)
 #define AND_GATE(q, U, V, Z) \
     t->send_d[0][q] = ((U)[0] ^ FIELD(q, 0)) & mask; t->send_d[1][q] = ((U)[1] ^ FIELD(q, 1)) & mask; \
     t->send_e[0][q] = ((V)[0] ^ FIELD(q, 2)) & mask; t->send_e[1][q] = ((V)[1] ^ FIELD(q, 3)) & mask; \
@@ -220,7 +258,7 @@ static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
     }
 
     /* B2A with one dealer bit r = rho0 ^ rho1, shared both ways */
-    const uint64_t Wb = hb_ref_sm(s->seedB, base + 5u * (uint64_t)(1 + 2 * s->R));
+    const uint64_t Wb = hb_ref_sm(s->seedB, base + b2a_word_of(s));
     const uint64_t rho0 = (Wb >> (2 * j)) & 1;
     const uint64_t rho1 = (Wb >> (2 * j + 1)) & 1;
     const uint64_t rbit = rho0 ^ rho1;
@@ -264,15 +302,16 @@ static void eval_element(const shape_t *s, uint64_t i, uint64_t x0, uint64_t x1,
 /* Elements first .. first+n-1 of a tensor; share0/share1/out0/out1 point at
  * element `first`.  what: 0 = DReLU shares, 1 = ReLU shares,
  * 2 = XOR shares of the full w-bit adder sum, 3 = XOR shares of the sign bit,
- * 4 = the sliced shares u0, u1. */
-int hb_ref_eval_range(const int64_t *share0, const int64_t *share1, uint64_t first, uint64_t n,
-                      int k, int m, uint64_t seed, int ring_bits, int what,
-                      int64_t *out0, int64_t *out1)
+ * 4 = the sliced shares u0, u1.
+ * variant: 0 = one triple per gate; 1 = the two gates of a prefix round share the mask of P. */
+int hb_ref_eval_range_v(const int64_t *share0, const int64_t *share1, uint64_t first, uint64_t n,
+                        int k, int m, uint64_t seed, int ring_bits, int variant, int what,
+                        int64_t *out0, int64_t *out1)
 {
     shape_t s;
     uint64_t i;
     if (what < 0 || what > 4) return HB_REF_EINVAL;
-    if (make_shape(&s, k, m, seed, ring_bits) != HB_REF_OK) return HB_REF_EINVAL;
+    if (make_shape_v(&s, k, m, seed, ring_bits, variant) != HB_REF_OK) return HB_REF_EINVAL;
     if (n > 0 && (!share0 || !share1 || !out0 || !out1)) return HB_REF_EINVAL;
     for (i = 0; i < n; i++) {
         elem_t t;
@@ -285,16 +324,23 @@ int hb_ref_eval_range(const int64_t *share0, const int64_t *share1, uint64_t fir
     return HB_REF_OK;
 }
 
+int hb_ref_eval_range(const int64_t *share0, const int64_t *share1, uint64_t first, uint64_t n,
+                      int k, int m, uint64_t seed, int ring_bits, int what,
+                      int64_t *out0, int64_t *out1)
+{
+    return hb_ref_eval_range_v(share0, share1, first, n, k, m, seed, ring_bits, 0, what, out0, out1);
+}
+
 /* Scattered elements: element index[i] of the tensor carries the share values
  * share0[i], share1[i].  Same `what` codes as above. */
-int hb_ref_eval_at(const int64_t *share0, const int64_t *share1, const uint64_t *index, uint64_t count,
-                   int k, int m, uint64_t seed, int ring_bits, int what,
-                   int64_t *out0, int64_t *out1)
+int hb_ref_eval_at_v(const int64_t *share0, const int64_t *share1, const uint64_t *index, uint64_t count,
+                     int k, int m, uint64_t seed, int ring_bits, int variant, int what,
+                     int64_t *out0, int64_t *out1)
 {
     shape_t s;
     uint64_t i;
     if (what < 0 || what > 4) return HB_REF_EINVAL;
-    if (make_shape(&s, k, m, seed, ring_bits) != HB_REF_OK) return HB_REF_EINVAL;
+    if (make_shape_v(&s, k, m, seed, ring_bits, variant) != HB_REF_OK) return HB_REF_EINVAL;
     if (count > 0 && (!share0 || !share1 || !index || !out0 || !out1)) return HB_REF_EINVAL;
     for (i = 0; i < count; i++) {
         elem_t t;
@@ -305,6 +351,13 @@ int hb_ref_eval_at(const int64_t *share0, const int64_t *share1, const uint64_t 
         out1[i] = (int64_t)src[1];
     }
     return HB_REF_OK;
+}
+
+int hb_ref_eval_at(const int64_t *share0, const int64_t *share1, const uint64_t *index, uint64_t count,
+                   int k, int m, uint64_t seed, int ring_bits, int what,
+                   int64_t *out0, int64_t *out1)
+{
+    return hb_ref_eval_at_v(share0, share1, index, count, k, m, seed, ring_bits, 0, what, out0, out1);
 }
 
 int hb_ref_drelu(const int64_t *share0, const int64_t *share1, uint64_t n, int k, int m,

@@ -29,16 +29,34 @@ def _bit(word, pos):
     return (word >> pos) & 1
 
 
-def _element_bitwise(i, x0, x1, k, m, seed, what):
+def _group_word_names(R, variant):
+    """The dealer words of one group, in stream order, as (gate, slot) names; slots 0..4 = a0 a1 b0 b1 c0."""
+    names = [(0, s) for s in range(5)]
+    for r in range(R):
+        g_gate, p_gate = 1 + 2 * r, 2 + 2 * r
+        if variant == 0:        # five words for every gate
+            names += [(g_gate, s) for s in range(5)] + [(p_gate, s) for s in range(5)]
+        else:                   # one mask of P for the round, then (b0 b1 c0) of each gate
+            names += [("mask", r, 0), ("mask", r, 1)]
+            names += [(g_gate, s) for s in (2, 3, 4)] + [(p_gate, s) for s in (2, 3, 4)]
+    names.append("b2a")
+    return names
+
+
+def _element_bitwise(i, x0, x1, k, m, seed, what, variant=0):
     w = m - k
     R = 0 if w == 1 else (w - 1).bit_length()
     L = min(64 // w, 32)
-    words_per_group = 5 * (1 + 2 * R) + 1
+    names = _group_word_names(R, variant)
+    words_per_group = len(names)
     seedB, seedA = _stream(seed, 0), _stream(seed, 1)
     g, lane = divmod(i, L)
 
     def dealer_bit(gate, slot, b):          # bit b of this element's field in that gate's word
-        return _bit(_stream(seedB, g * words_per_group + 5 * gate + slot), lane * w + b)
+        name = (gate, slot)
+        if variant == 1 and gate > 0 and slot < 2:
+            name = ("mask", (gate - 1) // 2, slot)
+        return _bit(_stream(seedB, g * words_per_group + names.index(name)), lane * w + b)
 
     def and_wire(gate, b, U, V):            # U, V: (party0 bit, party1 bit) on wire b
         a0, a1, b0, b1, c0 = [dealer_bit(gate, s, b) for s in range(5)]
@@ -71,7 +89,7 @@ def _element_bitwise(i, x0, x1, k, m, seed, what):
         cin = [zero] + G[:w - 1]
         return tuple(sum((S[b][p] ^ cin[b][p]) << b for b in range(w)) for p in (0, 1))
 
-    wb = _stream(seedB, g * words_per_group + 5 * (1 + 2 * R))
+    wb = _stream(seedB, g * words_per_group + names.index("b2a"))
     rho = (_bit(wb, 2 * lane), _bit(wb, 2 * lane + 1))
     z = sign[0] ^ sign[1] ^ rho[0] ^ rho[1]
     rA0 = _stream(seedA, 6 * i)
@@ -88,8 +106,9 @@ def _element_bitwise(i, x0, x1, k, m, seed, what):
     return ((c0 + eps * b0 + dlt * a0 + eps * dlt) & M64, (c1 + eps * b1 + dlt * a1) & M64)
 
 
+@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("k,m", [(12, 20), (0, 64), (8, 14), (8, 18), (3, 4), (0, 2), (5, 8), (20, 53), (8, 12), (0, 33), (7, 39)])
-def test_shares_match_bitwise_reading(k, m):
+def test_shares_match_bitwise_reading(k, m, variant):
     rng = np.random.default_rng(k * 64 + m)
     w = m - k
     L = min(64 // w, 32)
@@ -97,13 +116,13 @@ def test_shares_match_bitwise_reading(k, m):
     s0 = rng.integers(0, 1 << 64, n, dtype=np.uint64).view(np.int64)
     s1 = rng.integers(0, 1 << 64, n, dtype=np.uint64).view(np.int64)
     seed = 0xC0FFEE + m
-    d0, d1, _ = oracle.drelu(s0, s1, k, m, seed)
-    r0, r1, _ = oracle.relu(s0, s1, k, m, seed)
-    b0, b1 = oracle.evaluate(s0, s1, k, m, seed, oracle.WHAT_SUM)
+    d0, d1, _ = oracle.drelu(s0, s1, k, m, seed, variant=variant)
+    r0, r1, _ = oracle.relu(s0, s1, k, m, seed, variant=variant)
+    b0, b1 = oracle.evaluate(s0, s1, k, m, seed, oracle.WHAT_SUM, variant=variant)
     for i in range(n):
-        D = _element_bitwise(i, int(s0[i]), int(s1[i]), k, m, seed, "drelu")
-        Rl = _element_bitwise(i, int(s0[i]), int(s1[i]), k, m, seed, "relu")
-        B = _element_bitwise(i, int(s0[i]), int(s1[i]), k, m, seed, "sum")
+        D = _element_bitwise(i, int(s0[i]), int(s1[i]), k, m, seed, "drelu", variant)
+        Rl = _element_bitwise(i, int(s0[i]), int(s1[i]), k, m, seed, "relu", variant)
+        B = _element_bitwise(i, int(s0[i]), int(s1[i]), k, m, seed, "sum", variant)
         assert (int(b0[i]) & M64, int(b1[i]) & M64) == B, (i, k, m)
         assert (int(d0[i]) & M64, int(d1[i]) & M64) == D, (i, k, m)
         assert (int(r0[i]) & M64, int(r1[i]) & M64) == Rl, (i, k, m)

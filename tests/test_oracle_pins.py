@@ -151,6 +151,37 @@ def test_opened_bits_table_and_scaling():
     assert oracle.opened_bits(True, 3, 3, 5) == 0 and oracle.opened_bits(True, 0, 65, 5) == 0
 
 
+def test_opened_bits_shared_mask_variant():
+    """One mask for P per prefix round: that round opens P ^ a once and two second operands, 3w bits."""
+    for w in range(1, 65):
+        rounds = 0 if w == 1 else int(np.ceil(np.log2(w)))
+        per = 2 * w + 3 * w * rounds + 1
+        assert oracle.opened_bits(False, 0, w, 3, variant=1) == 3 * per
+        assert oracle.opened_bits(True, 64 - w, 64, 1, variant=1) == per + 128
+        saved = oracle.opened_bits(True, 0, w, 1) - oracle.opened_bits(True, 0, w, 1, variant=1)
+        assert saved == w * rounds
+    # the A2B share of the baseline's 1856 bits falls from 1536 to 1152 + 128 = 1280 (6 rounds of 64 bits saved)
+    assert oracle.opened_bits(True, 0, 64, 1, variant=1) == 1793 - 6 * 64
+    assert oracle.opened_bits(True, 12, 20, 1, variant=1) == 241 - 24
+
+
+def test_variants_differ_in_shares_only():
+    """The two dealer layouts give different shares of the same reconstructed values (and share gate 0's words)."""
+    rng = np.random.default_rng(77)
+    s0, s1 = _rand_shares(rng, 4000)
+    for (k, m) in [(12, 20), (0, 64), (8, 14), (0, 1)]:
+        a0, a1 = oracle.evaluate(s0, s1, k, m, SEED, oracle.WHAT_SUM, variant=0)
+        b0, b1 = oracle.evaluate(s0, s1, k, m, SEED, oracle.WHAT_SUM, variant=1)
+        assert np.array_equal(a0 ^ a1, b0 ^ b1)
+        if m - k > 1:
+            assert not np.array_equal(a0, b0)
+        r0, r1, _ = oracle.relu(s0, s1, k, m, SEED, variant=0)
+        q0, q1, _ = oracle.relu(s0, s1, k, m, SEED, variant=1)
+        assert np.array_equal(r0 + r1, q0 + q1)
+    with pytest.raises(ValueError):
+        oracle.evaluate(s0, s1, 12, 20, SEED, oracle.WHAT_SUM, variant=2)
+
+
 # ----------------------------------------------------------------------------------------------
 # the AND gate and the adder
 # ----------------------------------------------------------------------------------------------
@@ -172,8 +203,9 @@ def test_and_gate_words():
             assert z0 <= mask and z1 <= mask
 
 
+@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("w", range(1, 65))
-def test_adder_reconstructs_plain_sum_every_width(w):
+def test_adder_reconstructs_plain_sum_every_width(w, variant):
     """XOR of the two sum shares == (u0 + u1) mod 2^w in ALL w bits, for several k and many shares,
     at sizes that cover many dealer groups and a ragged last group."""
     rng = np.random.default_rng(1000 + w)
@@ -184,17 +216,18 @@ def test_adder_reconstructs_plain_sum_every_width(w):
         # extremes in front
         s0[:4] = np.array([0, -1, np.iinfo(np.int64).min, np.iinfo(np.int64).max])
         s1[:4] = np.array([-1, -1, np.iinfo(np.int64).min, 1])
-        b0, b1 = oracle.evaluate(s0, s1, k, k + w, SEED + w, oracle.WHAT_SUM)
+        b0, b1 = oracle.evaluate(s0, s1, k, k + w, SEED + w, oracle.WHAT_SUM, variant=variant)
         u0, u1 = _slice_np(s0, k, w), _slice_np(s1, k, w)
         got = _u64(b0) ^ _u64(b1)
         assert np.array_equal(got, _sum_mod_2w(u0, u1, w)), (w, k)
-        g0, g1 = oracle.evaluate(s0, s1, k, k + w, SEED + w, oracle.WHAT_SIGN)
+        g0, g1 = oracle.evaluate(s0, s1, k, k + w, SEED + w, oracle.WHAT_SIGN, variant=variant)
         assert np.array_equal(_u64(g0) ^ _u64(g1), got >> np.uint64(w - 1))
         assert set(np.unique(g0)) <= {0, 1} and set(np.unique(g1)) <= {0, 1}
 
 
+@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("w", range(1, 7))
-def test_adder_exhaustive_small_widths(w):
+def test_adder_exhaustive_small_widths(w, variant):
     vals = np.arange(1 << w, dtype=np.int64)
     u0, u1 = [a.reshape(-1) for a in np.meshgrid(vals, vals, indexing="ij")]
     rng = np.random.default_rng(w)
@@ -204,7 +237,7 @@ def test_adder_exhaustive_small_widths(w):
     for k in (0, 5):
         s0 = ((u0 | junk0) << k) | int(rng.integers(0, 1 << k)) if k else (u0 | junk0)
         s1 = ((u1 | junk1) << k) | int(rng.integers(0, 1 << k)) if k else (u1 | junk1)
-        b0, b1 = oracle.evaluate(s0, s1, k, k + w, SEED, oracle.WHAT_SUM)
+        b0, b1 = oracle.evaluate(s0, s1, k, k + w, SEED, oracle.WHAT_SUM, variant=variant)
         assert np.array_equal(b0 ^ b1, (u0 + u1) & ((1 << w) - 1))
 
 
@@ -217,7 +250,8 @@ def _shares_of(x, rng):
     return s0.view(np.int64), (x.view(np.uint64) - s0).view(np.int64)
 
 
-def test_full_ring_is_exact():
+@pytest.mark.parametrize("variant", [0, 1])
+def test_full_ring_is_exact(variant):
     """(k, m) = (0, 64): DReLU == [x >= 0] and ReLU == max(x, 0) for every x, including the extremes."""
     rng = np.random.default_rng(11)
     i64 = np.iinfo(np.int64)
@@ -227,15 +261,16 @@ def test_full_ring_is_exact():
         np.rint(rng.standard_normal(3000) * 2 * 65536).astype(np.int64),
     ])
     s0, s1 = _shares_of(x, rng)
-    d0, d1, bits = oracle.drelu(s0, s1, 0, 64, SEED)
+    d0, d1, bits = oracle.drelu(s0, s1, 0, 64, SEED, variant=variant)
     assert np.array_equal(d0 + d1, (x >= 0).astype(np.int64))
-    r0, r1, _ = oracle.relu(s0, s1, 0, 64, SEED)
+    r0, r1, _ = oracle.relu(s0, s1, 0, 64, SEED, variant=variant)
     assert np.array_equal(r0 + r1, np.maximum(x, 0))
-    assert bits == x.size * (oracle.opened_bits(True, 0, 64, 1) - 128)
+    assert bits == x.size * (oracle.opened_bits(True, 0, 64, 1, variant) - 128)
 
 
 @pytest.mark.parametrize("k,m", [(0, 64), (12, 20), (8, 16), (0, 1), (63, 64), (5, 38), (8, 14), (16, 26), (0, 33), (31, 64)])
-def test_beaver_identities_any_slice(k, m):
+@pytest.mark.parametrize("variant", [0, 1])
+def test_beaver_identities_any_slice(k, m, variant):
     """DReLU shares sum to 1 - MSB_w((u0 + u1) mod 2^w) in {0, 1}; ReLU shares sum to x * that, always."""
     rng = np.random.default_rng(k * 100 + m)
     n = 5000
@@ -245,9 +280,9 @@ def test_beaver_identities_any_slice(k, m):
     w = m - k
     msb = _sum_mod_2w(_slice_np(s0, k, w), _slice_np(s1, k, w), w) >> np.uint64(w - 1)
     expect_d = (1 - msb.astype(np.int64))
-    d0, d1, _ = oracle.drelu(s0, s1, k, m, SEED)
+    d0, d1, _ = oracle.drelu(s0, s1, k, m, SEED, variant=variant)
     assert np.array_equal(d0 + d1, expect_d)
-    r0, r1, _ = oracle.relu(s0, s1, k, m, SEED)
+    r0, r1, _ = oracle.relu(s0, s1, k, m, SEED, variant=variant)
     assert np.array_equal(r0 + r1, x * expect_d)
     # the DReLU shares inside hb_relu are the ones hb_drelu returns: ReLU opens delta = DReLU - b
     # (checked indirectly: same reconstructed product for every element)
@@ -293,7 +328,8 @@ def test_theorem2_low_cut_prunes_small_positives_only():
 # brute force on the 8-bit ring: every share pair, every (k, m)
 # ----------------------------------------------------------------------------------------------
 
-def test_brute_force_ring8_error_set():
+@pytest.mark.parametrize("variant", [0, 1])
+def test_brute_force_ring8_error_set(variant):
     N = 8
     v = np.arange(256, dtype=np.int64)
     s0, s1 = [a.reshape(-1) for a in np.meshgrid(v, v, indexing="ij")]
@@ -304,10 +340,10 @@ def test_brute_force_ring8_error_set():
     for k in range(N):
         for m in range(k + 1, N + 1):
             w = m - k
-            d0, d1, _ = oracle.drelu(s0, s1, k, m, SEED, ring_bits=N)
+            d0, d1, _ = oracle.drelu(s0, s1, k, m, SEED, ring_bits=N, variant=variant)
             d = (d0 + d1) & 255
             assert set(np.unique(d)) <= {0, 1}
-            r0, r1, _ = oracle.relu(s0, s1, k, m, SEED, ring_bits=N)
+            r0, r1, _ = oracle.relu(s0, s1, k, m, SEED, ring_bits=N, variant=variant)
             r = (r0 + r1) & 255
             assert np.array_equal(r, (xs * d) & 255)
 
