@@ -137,6 +137,11 @@ def main():
                 hb.hb_relu(a, b, spec.k, spec.m, seed, c, d)
         ms = _time_launches(per_tensor_step, 40, torch)
         extra["relu_w8_elems_per_s_one_launch_per_tensor"] = n_total / (ms * 1e-3)
+        # the same set on the shared-mask dealer layout (3w opened bits per prefix round, 4 dealer words fewer per group)
+        ms = _time_launches(lambda: hb.hb_relu_batch_ex(batch, hb.HB_DEALER_SHARED_MASK), 60, torch)
+        extra["relu_w8_shared_mask_elems_per_s"] = n_total / (ms * 1e-3)
+        extra["relu_w8_shared_mask_hbm_frac"] = BYTES_PER_ELEMENT * n_total / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+        extra["relu_w8_shared_mask_opened_bits_per_element"] = hb.hb_opened_bits_ex(True, k, m, 1, hb.HB_DEALER_SHARED_MASK)
         ms = _time_launches(lambda: hb.hb_relu(s0, s1, 0, 64, seed0, o0, o1), 60, torch)
         extra["relu_w64_elems_per_s"] = spec0.n / (ms * 1e-3)
         extra["relu_w64_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS

@@ -107,6 +107,28 @@ HB_API int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opene
 HB_API int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream);
 
 /*
+ * Dealer layouts.  In a prefix round of the adder (Sec. 2.2, Sec. 4.2) both AND gates have the old propagate
+ * word P as their first operand.  HB_DEALER_PER_GATE gives every gate its own Beaver triple (the plain reading:
+ * 4w opened bits per round).  HB_DEALER_SHARED_MASK lets the two gates of a round share the mask a of P, with
+ * triples (a, b, a&b) and (a, b', a&b'): P ^ a is opened once and the round opens 3w bits.  The circuit and
+ * every reconstructed value are the same; the individual output shares differ between the layouts.
+ * Shared-mask words of one group, in stream order: gate 0 (a_0 a_1 b_0 b_1 c_0); per round a_0 a_1, then
+ * b_0 b_1 c_0 of the G-update, then b_0 b_1 c_0 of the P-update; then the B2A word.
+ *
+ * The *_ex entry points are hb_drelu / hb_relu / hb_relu_batch / hb_drelu_batch with the layout as an argument
+ * (`dealer`; any other value is HB_EINVAL); with HB_DEALER_PER_GATE they are those calls bit for bit.
+ */
+#define HB_DEALER_PER_GATE 0
+#define HB_DEALER_SHARED_MASK 1
+
+HB_API int hb_drelu_ex(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int dealer,
+                       int64_t *out0, int64_t *out1, uint64_t *opened_bits, void *stream);
+HB_API int hb_relu_ex(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int dealer,
+                      int64_t *out0, int64_t *out1, uint64_t *opened_bits, void *stream);
+HB_API int hb_relu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64_t *opened_bits, void *stream);
+HB_API int hb_drelu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64_t *opened_bits, void *stream);
+
+/*
  * Party-faithful ReLU: the same protocol and dealer material as hb_relu, but every opening goes through
  * memory the way it would go over the link between two GPUs (Sec. 2.2: each AND, the B2A and the multiply
  * open masked values; Sec. 4.2: the w-bit fields are packed into 64-bit words before each communication).
@@ -176,6 +198,9 @@ HB_API uint64_t hb_tensor_seed(uint64_t root_seed, uint64_t tensor_id);
  * of Sec. 2.3 is 29 * 64 = 1856 bits per element.  Returns 0 for an invalid (k, m).
  */
 HB_API uint64_t hb_opened_bits(int relu, int k, int m, size_t n);
+
+/* The same count for a dealer layout: HB_DEALER_SHARED_MASK opens n * (2w + 3wR + 1) (+ 128 n).  0 for an unknown layout. */
+HB_API uint64_t hb_opened_bits_ex(int relu, int k, int m, size_t n, int dealer);
 
 /* Static description of a status code. */
 HB_API const char *hb_strerror(int status);

@@ -25,7 +25,7 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 
-MODES = (0, 1, 2)                                       # DReLU, ReLU, sign shares
+MODES = (0, 1, 2, 3, 4)                                 # DReLU, ReLU, sign shares; DReLU, ReLU on the shared-mask layout
 WIDTH_RANGES = ((1, 16), (17, 32), (33, 48), (49, 64))
 
 

@@ -132,6 +132,20 @@ int validate_tensor(const int64_t *share0, const int64_t *share1, size_t n, int 
     return HB_OK;
 }
 
+uint64_t mode_bits(int mode, int k, int m, size_t n)
+{
+    return hb_opened_bits_ex(hb::op_of(mode) == hb::kRelu, k, m, n,
+                             hb::shared_of(mode) ? HB_DEALER_SHARED_MASK : HB_DEALER_PER_GATE);
+}
+
+// mode of an operation (kDrelu or kRelu) on a dealer layout; -1 for an unknown layout
+int mode_on(int op, int dealer)
+{
+    if (dealer == HB_DEALER_PER_GATE) return op;
+    if (dealer == HB_DEALER_SHARED_MASK) return op + hb::kDreluShared;
+    return -1;
+}
+
 int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
         int64_t *out1, uint64_t *opened_bits, void *stream)
 {
@@ -143,7 +157,7 @@ int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k,
     if (mode == hb::kSign) {
         bits = (uint64_t)n * (2ull * (uint64_t)w * (1 + 2 * (uint64_t)rounds_of(w)));
     } else {
-        bits = hb_opened_bits(mode == hb::kRelu, k, m, n);
+        bits = mode_bits(mode, k, m, n);
     }
     if (n > 0) {
         const uint64_t seedB = hb::stream_word(seed, 0), seedA = hb::stream_word(seed, 1);
@@ -214,7 +228,7 @@ int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened
         const hb_tensor &first = tensors[i];
         const int w = first.m - first.k;
         taken[i] = true;
-        bits += hb_opened_bits(mode == hb::kRelu, first.k, first.m, first.n);
+        bits += mode_bits(mode, first.k, first.m, first.n);
         if (first.n == 0) continue;
         const hb::BatchLauncher bl = hb::launcher_table().batch[mode][w - 1];
         const void *p0[4] = {first.share0, first.share1, first.out0, first.out1};
@@ -258,7 +272,7 @@ int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened
                 if (st != HB_OK) return st;
             }
             taken[j] = true;
-            bits += hb_opened_bits(mode == hb::kRelu, t.k, t.m, t.n);
+            bits += mode_bits(mode, t.k, t.m, t.n);
             add(t);
         }
         const int st = flush();
@@ -315,6 +329,36 @@ int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits,
 int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
 {
     return run_batch(hb::kDrelu, tensors, count, opened_bits, stream);
+}
+
+int hb_drelu_ex(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int dealer,
+                int64_t *out0, int64_t *out1, uint64_t *opened_bits, void *stream)
+{
+    const int mode = mode_on(hb::kDrelu, dealer);
+    if (mode < 0) return HB_EINVAL;
+    return run(mode, share0, share1, n, k, m, seed, out0, out1, opened_bits, stream);
+}
+
+int hb_relu_ex(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int dealer,
+               int64_t *out0, int64_t *out1, uint64_t *opened_bits, void *stream)
+{
+    const int mode = mode_on(hb::kRelu, dealer);
+    if (mode < 0) return HB_EINVAL;
+    return run(mode, share0, share1, n, k, m, seed, out0, out1, opened_bits, stream);
+}
+
+int hb_relu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64_t *opened_bits, void *stream)
+{
+    const int mode = mode_on(hb::kRelu, dealer);
+    if (mode < 0) return HB_EINVAL;
+    return run_batch(mode, tensors, count, opened_bits, stream);
+}
+
+int hb_drelu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64_t *opened_bits, void *stream)
+{
+    const int mode = mode_on(hb::kDrelu, dealer);
+    if (mode < 0) return HB_EINVAL;
+    return run_batch(mode, tensors, count, opened_bits, stream);
 }
 
 size_t hb_party_wire_words(size_t n, int k, int m)
@@ -554,9 +598,16 @@ uint64_t hb_tensor_seed(uint64_t root_seed, uint64_t tensor_id) { return hb::str
 
 uint64_t hb_opened_bits(int relu, int k, int m, size_t n)
 {
-    if (!valid_slice(k, m)) return 0;
-    const uint64_t w = (uint64_t)(m - k);
-    const uint64_t per = 2 * w * (1 + 2 * (uint64_t)rounds_of((int)w)) + 1 + (relu ? 128 : 0);
+    return hb_opened_bits_ex(relu, k, m, n, HB_DEALER_PER_GATE);
+}
+
+uint64_t hb_opened_bits_ex(int relu, int k, int m, size_t n, int dealer)
+{
+    if (!valid_slice(k, m) || (dealer != HB_DEALER_PER_GATE && dealer != HB_DEALER_SHARED_MASK)) return 0;
+    const uint64_t w = (uint64_t)(m - k), R = (uint64_t)rounds_of((int)w);
+    // gate 0 opens 2w bits; a prefix round opens 4w, or 3w when its two gates share the mask of P
+    const uint64_t per_round = dealer == HB_DEALER_SHARED_MASK ? 3 * w : 4 * w;
+    const uint64_t per = 2 * w + per_round * R + 1 + (relu ? 128 : 0);
     return (uint64_t)n * per;
 }
 

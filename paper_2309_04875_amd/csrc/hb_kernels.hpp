@@ -33,7 +33,7 @@ group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups
     using S = Shape<W>;
     constexpr int L = S::L;
     // keep the loaded shares in registers across the circuit when that is cheap, else read them again
-    constexpr bool kHold = (MODE == kRelu) && (L <= 8);
+    constexpr bool kHold = (op_of(MODE) == kRelu) && (L <= 8);
 
     const uint64_t g = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     if (g >= groups) return;
@@ -78,10 +78,10 @@ group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups
         }
     }
 
-    const uint64_t zg = seedB + (g * (uint64_t)S::kWordsPerGroup + 1) * kGamma;
-    const Pair sum = a2b_sum<W>(u0, u1, zg);
+    const uint64_t zg = seedB + (g * (uint64_t)S::words_per_group(shared_of(MODE)) + 1) * kGamma;
+    const Pair sum = a2b_sum<W, shared_of(MODE)>(u0, u1, zg);
     uint64_t wb = 0;
-    if (MODE != kSign) wb = mix64(zg + (uint64_t)(5 * S::kGates) * kGamma);
+    if (op_of(MODE) != kSign) wb = mix64(zg + (uint64_t)S::b2a_word(shared_of(MODE)) * kGamma);
 
     const uint64_t zA0 = seedA + (6 * i0 + 1) * kGamma;
     if (VEC && full && (L % 2 == 0)) {
@@ -90,7 +90,7 @@ group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups
 #pragma unroll
         for (int j = 0; j < L / 2; ++j) {
             Pair xe{0, 0}, xo{0, 0};
-            if (MODE == kRelu) {
+            if (op_of(MODE) == kRelu) {
                 if (kHold) {
                     xe = Pair{xa[2 * j], xb[2 * j]};
                     xo = Pair{xa[2 * j + 1], xb[2 * j + 1]};
@@ -111,7 +111,7 @@ group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups
         for (int j = 0; j < L; ++j) {
             if (j < cnt) {
                 Pair x{0, 0};
-                if (MODE == kRelu) x = kHold ? Pair{xa[j], xb[j]} : Pair{x0[i0 + j], x1[i0 + j]};
+                if (op_of(MODE) == kRelu) x = kHold ? Pair{xa[j], xb[j]} : Pair{x0[i0 + j], x1[i0 + j]};
                 const Pair r = finish_element<W, MODE>(sum, wb, j, x, zA0 + (uint64_t)(6 * j) * kGamma);
                 o0[i0 + j] = r.p0;
                 o1[i0 + j] = r.p1;
@@ -324,14 +324,14 @@ __device__ __forceinline__ void tile_body(const IO &io, uint64_t n, int k, uint6
         }
     }
     const uint64_t g = tile * kWave + lane;
-    const uint64_t zg = seedB + (g * (uint64_t)S::kWordsPerGroup + 1) * kGamma;
-    const Pair sum = a2b_sum<W>(u0, u1, zg);
+    const uint64_t zg = seedB + (g * (uint64_t)S::words_per_group(shared_of(MODE)) + 1) * kGamma;
+    const Pair sum = a2b_sum<W, shared_of(MODE)>(u0, u1, zg);
     {
         // sign of field j: party 0 at bit jW, party 1 at bit jW + 1
         const uint64_t ones = S::ones();
         const uint64_t sg = ((sum.p0 >> (W - 1)) & ones) | (((sum.p1 >> (W - 1)) & ones) << 1);
         uint64_t wb = 0;
-        if (MODE != kSign) wb = mix64(zg + (uint64_t)(5 * S::kGates) * kGamma);
+        if (op_of(MODE) != kSign) wb = mix64(zg + (uint64_t)S::b2a_word(shared_of(MODE)) * kGamma);
         verdict[lane] = U64x2{sg, wb};
     }
     wave_sync();
@@ -356,14 +356,14 @@ __device__ __forceinline__ void tile_body(const IO &io, uint64_t n, int k, uint6
                 // only bits 0 and 1 of each shifted word are used
                 const uint32_t sg = (uint32_t)(v.a >> (j * W));
                 const Pair sign{sg & 1u, (sg >> 1) & 1u};
-                if (MODE == kSign) {
+                if (op_of(MODE) == kSign) {
                     r[h] = sign;
                 } else {
                     const uint32_t rh = (uint32_t)(v.b >> (2 * j));
                     const Pair rho{rh & 1u, (rh >> 1) & 1u};
                     const uint64_t zA = zA0 + (uint64_t)(6 * (2 * c * kWave + h)) * kGamma;
                     const Pair D = b2a_drelu(sign, rho, zA);
-                    r[h] = (MODE == kDrelu) ? D : beaver_mul(Pair{h ? xa[c].b : xa[c].a, h ? xb[c].b : xb[c].a}, D, zA);
+                    r[h] = (op_of(MODE) == kDrelu) ? D : beaver_mul(Pair{h ? xa[c].b : xa[c].a, h ? xb[c].b : xb[c].a}, D, zA);
                 }
             }
             io.store_pair(i, n, r[0], r[1]);

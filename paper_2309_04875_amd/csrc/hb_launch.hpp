@@ -21,9 +21,9 @@ using SimLauncher = hipError_t (*)(const float *x, uint64_t n, int k, uint64_t s
                                    float *y, hipStream_t stream);
 
 struct LauncherTable {
-    GroupLauncher f[3][64];       // [mode][w - 1]
-    BatchLauncher batch[3][64];   // null where the width has no tile kernel
-    SimLauncher sim[64];          // null where the width has no tile kernel
+    GroupLauncher f[kModes][64];       // [mode][w - 1]
+    BatchLauncher batch[kModes][64];   // null where the width has no tile kernel
+    SimLauncher sim[64];               // null where the width has no tile kernel
 };
 
 LauncherTable &launcher_table();

@@ -4,7 +4,7 @@
 #include "hb_launch.hpp"
 
 #if !defined(HB_PART_MODE) || !defined(HB_PART_LO) || !defined(HB_PART_HI)
-#error "compile with -DHB_PART_MODE=<0|1|2> -DHB_PART_LO=<w> -DHB_PART_HI=<w>"
+#error "compile with -DHB_PART_MODE=<0..4> -DHB_PART_LO=<w> -DHB_PART_HI=<w>"
 #endif
 
 namespace {

@@ -41,7 +41,13 @@ struct Shape {
     static constexpr int R = ceil_log2(W);                     // prefix rounds (0 when W == 1)
     static constexpr int L = (64 / W) > 32 ? 32 : (64 / W);     // fields per word
     static constexpr int kGates = 1 + 2 * R;                    // gate 0 + two per round
-    static constexpr int kWordsPerGroup = 5 * kGates + 1;       // five triple words per gate + the B2A word
+
+    // Dealer words of one group.  Standard layout: five triple words (a_0 a_1 b_0 b_1 c_0) per gate, then the
+    // B2A word.  Shared-mask layout: gate 0 as before; a prefix round owns eight words, a_0 a_1 (the one mask of
+    // P that both of its gates use), b_0 b_1 c_0 of the G-update and b_0 b_1 c_0 of the P-update; then the B2A word.
+    static constexpr int round_word(bool shared, int r) { return shared ? 5 + 8 * r : 5 * (1 + 2 * r); }
+    static constexpr int b2a_word(bool shared) { return round_word(shared, R); }
+    static constexpr int words_per_group(bool shared) { return b2a_word(shared) + 1; }
     static constexpr uint64_t kField = (W == 64) ? ~0ull : ((1ull << (W & 63)) - 1);
 
     // bit 0 of every field
@@ -85,11 +91,45 @@ __device__ __forceinline__ Pair beaver_and(uint64_t zq, Pair U, Pair V)
     return Z;
 }
 
+// The two Beaver ANDs of a prefix round when one mask serves their common first operand U: T = U & V, Q = U & Y.
+// zr is the generator state of the round's first word; the eight words a_0 a_1 | b_0 b_1 c_0 (for V) |
+// b_0 b_1 c_0 (for Y) are consecutive outputs.  d = U ^ a is opened once.  With kSecond false only the first
+// gate is evaluated and its three last words are never drawn.
+template <bool kSecond>
+__device__ __forceinline__ void beaver_and_shared(uint64_t zr, Pair U, Pair V, Pair Y, Pair &T, Pair &Q)
+{
+    const uint64_t a0 = mix64(zr);
+    const uint64_t a1 = mix64(zr + 1 * kGamma);
+    const uint64_t a = a0 ^ a1;
+    const uint64_t d = (U.p0 ^ U.p1) ^ a;
+    {
+        const uint64_t b0 = mix64(zr + 2 * kGamma);
+        const uint64_t b1 = mix64(zr + 3 * kGamma);
+        const uint64_t c0 = mix64(zr + 4 * kGamma);
+        const uint64_t b = b0 ^ b1;
+        const uint64_t c1 = (a & b) ^ c0;
+        const uint64_t e = (V.p0 ^ V.p1) ^ b;
+        T.p0 = c0 ^ (d & (b0 ^ e)) ^ (e & a0);
+        T.p1 = c1 ^ (d & b1) ^ (e & a1);
+    }
+    if (kSecond) {
+        const uint64_t b0 = mix64(zr + 5 * kGamma);
+        const uint64_t b1 = mix64(zr + 6 * kGamma);
+        const uint64_t c0 = mix64(zr + 7 * kGamma);
+        const uint64_t b = b0 ^ b1;
+        const uint64_t c1 = (a & b) ^ c0;
+        const uint64_t e = (Y.p0 ^ Y.p1) ^ b;
+        Q.p0 = c0 ^ (d & (b0 ^ e)) ^ (e & a0);
+        Q.p1 = c1 ^ (d & b1) ^ (e & a1);
+    }
+}
+
 // A2B + sign for one group.  u0/u1: the L sliced shares of party 0 / party 1 packed as fields.
 // zg: generator state of the group's first dealer word.  Returns XOR shares of the sum word
 // S ^ (G << 1); the sign of field j is bit jW + W - 1.  The last round's P-update gate is not
-// evaluated: nothing reads its result (its dealer words are simply never drawn).
-template <int W>
+// evaluated: nothing reads its result (its dealer words are simply never drawn).  SHARED selects the
+// dealer layout in which the two gates of a round share the mask of P.
+template <int W, bool SHARED>
 __device__ __forceinline__ Pair a2b_sum(uint64_t u0, uint64_t u1, uint64_t zg)
 {
     using S = Shape<W>;
@@ -103,10 +143,17 @@ __device__ __forceinline__ Pair a2b_sum(uint64_t u0, uint64_t u1, uint64_t zg)
         const int s = 1 << r;
         const uint64_t keep = S::keep(s);
         const Pair Gs{(G.p0 << s) & keep, (G.p1 << s) & keep};
-        const Pair T = beaver_and(zg + (uint64_t)(5 * (1 + 2 * r)) * kGamma, P, Gs);
-        if (r + 1 < S::R) {
-            const Pair Ps{(P.p0 << s) & keep, (P.p1 << s) & keep};
-            P = beaver_and(zg + (uint64_t)(5 * (2 + 2 * r)) * kGamma, P, Ps);
+        const Pair Ps{(P.p0 << s) & keep, (P.p1 << s) & keep};
+        const uint64_t zr = zg + (uint64_t)S::round_word(SHARED, r) * kGamma;
+        Pair T;
+        if (SHARED) {
+            Pair Pn = P;
+            if (r + 1 < S::R) beaver_and_shared<true>(zr, P, Gs, Ps, T, Pn);
+            else beaver_and_shared<false>(zr, P, Gs, Ps, T, Pn);
+            P = Pn;
+        } else {
+            T = beaver_and(zr, P, Gs);
+            if (r + 1 < S::R) P = beaver_and(zr + 5 * kGamma, P, Ps);
         }
         G.p0 ^= T.p0;
         G.p1 ^= T.p1;
@@ -146,7 +193,11 @@ __device__ __forceinline__ Pair beaver_mul(Pair x, Pair D, uint64_t zA)
     return out;
 }
 
-enum Mode { kDrelu = 0, kRelu = 1, kSign = 2 };
+// What a launch computes.  The two last modes run the same operation on the shared-mask dealer layout.
+enum Mode { kDrelu = 0, kRelu = 1, kSign = 2, kDreluShared = 3, kReluShared = 4, kModes = 5 };
+
+constexpr int op_of(int mode) { return mode >= kDreluShared ? mode - kDreluShared : mode; }
+constexpr bool shared_of(int mode) { return mode >= kDreluShared; }
 
 // Everything after the circuit for element j of a group: pick the element's sign and dealer bits
 // out of the group words, B2A, multiply.
@@ -155,10 +206,10 @@ __device__ __forceinline__ Pair finish_element(Pair sum, uint64_t wb, int j, Pai
 {
     const int sb = j * W + W - 1;
     const Pair sign{(sum.p0 >> sb) & 1, (sum.p1 >> sb) & 1};
-    if (MODE == kSign) return sign;
+    if (op_of(MODE) == kSign) return sign;
     const Pair rho{(wb >> (2 * j)) & 1, (wb >> (2 * j + 1)) & 1};
     const Pair D = b2a_drelu(sign, rho, zA);
-    if (MODE == kDrelu) return D;
+    if (op_of(MODE) == kDrelu) return D;
     return beaver_mul(x, D, zA);
 }
 

@@ -11,12 +11,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIBRARY = os.path.join(HERE, "libhb.so")
 
 HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP, HB_ENOTSUP = 0, -1, -2, -3, -4
+HB_DEALER_PER_GATE, HB_DEALER_SHARED_MASK = 0, 1
 BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accounting
 
 EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_eco_scan", "hb_eco_choose",
            "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
+           "hb_drelu_ex", "hb_relu_ex", "hb_relu_batch_ex", "hb_drelu_batch_ex",
            "hb_tensor_seed",
-           "hb_opened_bits", "hb_strerror", "hb_last_hip_error")
+           "hb_opened_bits", "hb_opened_bits_ex", "hb_strerror", "hb_last_hip_error")
 
 _lib = None
 
@@ -53,6 +55,16 @@ def load():
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [ctypes.POINTER(hb_tensor), sz, u64p, vp]
+    for name in ("hb_drelu_ex", "hb_relu_ex"):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [vp, vp, sz, ci, ci, u64, ci, vp, vp, u64p, vp]
+    for name in ("hb_relu_batch_ex", "hb_drelu_batch_ex"):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [ctypes.POINTER(hb_tensor), sz, ci, u64p, vp]
+    lib.hb_opened_bits_ex.restype = u64
+    lib.hb_opened_bits_ex.argtypes = [ci, ci, ci, sz, ci]
     lib.hb_share_f32.restype = ci
     lib.hb_share_f32.argtypes = [vp, sz, u64, vp, vp, vp]
     lib.hb_reveal_f32.restype = ci
@@ -119,7 +131,7 @@ def _stream_handle(stream):
     return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
 
 
-def _shares_call(name, share0, share1, k, m, seed, out0, out1, stream):
+def _shares_call(name, share0, share1, k, m, seed, out0, out1, stream, dealer=None):
     import torch
     if out0 is None:
         out0 = torch.empty_like(share0)
@@ -127,8 +139,9 @@ def _shares_call(name, share0, share1, k, m, seed, out0, out1, stream):
         out1 = torch.empty_like(share1)
     n = _tensor_args(share0, share1, out0, out1)
     bits = ctypes.c_uint64(0)
+    layout = () if dealer is None else (int(dealer),)
     st = getattr(load(), name)(share0.data_ptr(), share1.data_ptr(), n, int(k), int(m), int(seed) & (2**64 - 1),
-                               out0.data_ptr(), out1.data_ptr(), ctypes.byref(bits), _stream_handle(stream))
+                               *layout, out0.data_ptr(), out1.data_ptr(), ctypes.byref(bits), _stream_handle(stream))
     _check(st)
     return out0, out1, int(bits.value)
 
@@ -141,6 +154,16 @@ def hb_drelu(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
 def hb_relu(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
     """Arithmetic shares of x * DReLU; returns (out0, out1, opened_bits)."""
     return _shares_call("hb_relu", share0, share1, k, m, seed, out0, out1, stream)
+
+
+def hb_drelu_ex(share0, share1, k, m, seed, dealer, out0=None, out1=None, stream=None):
+    """hb_drelu on the dealer layout `dealer` (HB_DEALER_PER_GATE or HB_DEALER_SHARED_MASK)."""
+    return _shares_call("hb_drelu_ex", share0, share1, k, m, seed, out0, out1, stream, dealer)
+
+
+def hb_relu_ex(share0, share1, k, m, seed, dealer, out0=None, out1=None, stream=None):
+    """hb_relu on the dealer layout `dealer`."""
+    return _shares_call("hb_relu_ex", share0, share1, k, m, seed, out0, out1, stream, dealer)
 
 
 def hb_sign_shares(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
@@ -158,11 +181,12 @@ def make_batch(items):
     return arr
 
 
-def _batch_call(name, batch, stream):
+def _batch_call(name, batch, stream, dealer=None):
     if not isinstance(batch, ctypes.Array):
         batch = make_batch(batch)
     bits = ctypes.c_uint64(0)
-    _check(getattr(load(), name)(batch, len(batch), ctypes.byref(bits), _stream_handle(stream)))
+    layout = () if dealer is None else (int(dealer),)
+    _check(getattr(load(), name)(batch, len(batch), *layout, ctypes.byref(bits), _stream_handle(stream)))
     return int(bits.value)
 
 
@@ -174,6 +198,14 @@ def hb_relu_batch(batch, stream=None):
 
 def hb_drelu_batch(batch, stream=None):
     return _batch_call("hb_drelu_batch", batch, stream)
+
+
+def hb_relu_batch_ex(batch, dealer, stream=None):
+    return _batch_call("hb_relu_batch_ex", batch, stream, dealer)
+
+
+def hb_drelu_batch_ex(batch, dealer, stream=None):
+    return _batch_call("hb_drelu_batch_ex", batch, stream, dealer)
 
 
 def _float_arg(t):
@@ -301,6 +333,10 @@ def hb_tensor_seed(root_seed, tensor_id):
 
 def hb_opened_bits(relu, k, m, n):
     return int(load().hb_opened_bits(int(bool(relu)), int(k), int(m), int(n)))
+
+
+def hb_opened_bits_ex(relu, k, m, n, dealer):
+    return int(load().hb_opened_bits_ex(int(bool(relu)), int(k), int(m), int(n), int(dealer)))
 
 
 def raw(name, *args):
