@@ -62,6 +62,13 @@ def lib():
         L.hb_ref_reveal_f32.argtypes = [_i64p, _i64p, _u64, _f32p]
         L.hb_ref_open.restype = _int
         L.hb_ref_open.argtypes = [_i64p, _i64p, _u64, _int, _int, _i64p]
+        _pp = ctypes.POINTER(_i64p)
+        L.hb_ref_mp_opened_bits.restype = _u64
+        L.hb_ref_mp_opened_bits.argtypes = [_int, _int, _int, _int, _u64]
+        L.hb_ref_mp_eval_range.restype = _int
+        L.hb_ref_mp_eval_range.argtypes = [_pp, _int, _u64, _u64, _int, _int, _u64, _int, _int, _pp]
+        L.hb_ref_mp_eval_at.restype = _int
+        L.hb_ref_mp_eval_at.argtypes = [_pp, _int, _u64p, _u64, _int, _int, _u64, _int, _int, _pp]
         _lib = L
     return _lib
 
@@ -241,3 +248,65 @@ def sim_relu_f32(x, k, m, seed, share_seed, threads=1):
     s0, s1 = share_f32(x, share_seed)
     r0, r1, _ = relu(s0, s1, k, m, seed, threads=threads)
     return reveal_f32(r0, r1)
+
+
+# ---- p >= 2 parties (oracle/hb_ref_mp.c) ------------------------------------------------------------------
+
+def mp_opened_bits(relu, parties, k, m, n):
+    """Bits one party sends to one other party."""
+    return int(lib().hb_ref_mp_opened_bits(int(bool(relu)), parties, k, m, _u64(n)))
+
+
+def _pointer_table(arrays, lo=0, hi=None):
+    tab = (_i64p * len(arrays))()
+    for q, a in enumerate(arrays):
+        tab[q] = _ptr(a[lo:hi])
+    return tab
+
+
+def mp_evaluate(shares, k, m, seed, what, ring_bits=64, first=0, threads=1):
+    """The protocol among len(shares) parties on whole arrays; returns the list of per-party arrays chosen by `what`."""
+    sh = [_as_i64(a) for a in shares]
+    p, n = len(sh), sh[0].size
+    if any(a.size != n for a in sh):
+        raise ValueError("share arrays differ in length")
+    outs = [np.empty(n, dtype=np.int64) for _ in range(p)]
+    L = lib()
+
+    def run(lo, hi):
+        st = L.hb_ref_mp_eval_range(_pointer_table(sh, lo, hi), p, _u64(first + lo), _u64(hi - lo), k, m,
+                                    _u64(seed & (2**64 - 1)), ring_bits, what, _pointer_table(outs, lo, hi))
+        if st != 0:
+            raise ValueError("oracle rejected arguments (status %d)" % st)
+
+    threads = max(1, int(threads))
+    if threads == 1 or n < 4096:
+        run(0, n)
+    else:
+        bounds = np.linspace(0, n, threads + 1).astype(np.int64)
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            list(pool.map(lambda ab: run(int(ab[0]), int(ab[1])), zip(bounds[:-1], bounds[1:])))
+    return outs
+
+
+def mp_evaluate_at(shares, index, k, m, seed, what, ring_bits=64):
+    sh = [_as_i64(a) for a in shares]
+    idx = np.ascontiguousarray(index, dtype=np.uint64).reshape(-1)
+    if any(a.size != idx.size for a in sh):
+        raise ValueError("length mismatch")
+    outs = [np.empty(idx.size, dtype=np.int64) for _ in range(len(sh))]
+    st = lib().hb_ref_mp_eval_at(_pointer_table(sh), len(sh), _ptr(idx, _u64p), _u64(idx.size), k, m,
+                                 _u64(seed & (2**64 - 1)), ring_bits, what, _pointer_table(outs))
+    if st != 0:
+        raise ValueError("oracle rejected arguments (status %d)" % st)
+    return outs
+
+
+def mp_drelu(shares, k, m, seed, ring_bits=64, threads=1):
+    outs = mp_evaluate(shares, k, m, seed, WHAT_DRELU, ring_bits, threads=threads)
+    return outs, mp_opened_bits(False, len(outs), k, m, outs[0].size)
+
+
+def mp_relu(shares, k, m, seed, ring_bits=64, threads=1):
+    outs = mp_evaluate(shares, k, m, seed, WHAT_RELU, ring_bits, threads=threads)
+    return outs, mp_opened_bits(True, len(outs), k, m, outs[0].size)

@@ -7,15 +7,15 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCE = os.path.join(HERE, "hb_ref.c")
+SOURCES = [os.path.join(HERE, "hb_ref.c"), os.path.join(HERE, "hb_ref_mp.c")]
 LIBRARY = os.path.join(HERE, "libhb_ref.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIBRARY) and os.path.getmtime(LIBRARY) >= os.path.getmtime(SOURCE):
+    if not force and os.path.exists(LIBRARY) and all(os.path.getmtime(LIBRARY) >= os.path.getmtime(f) for f in SOURCES):
         return LIBRARY
     tmp = LIBRARY + ".tmp.%d" % os.getpid()
-    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", SOURCE, "-o", tmp, "-lm"]
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared"] + SOURCES + ["-o", tmp, "-lm"]
     subprocess.run(cmd, check=True)
     os.replace(tmp, LIBRARY)
     return LIBRARY
