@@ -129,6 +129,31 @@ HB_API int hb_relu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, 
 HB_API int hb_drelu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64_t *opened_bits, void *stream);
 
 /*
+ * More than two parties (Sec. 2.2 "Operation of CrypTen": a secret is split into p >= 2 arithmetic shares;
+ * Sec. 3.1.2: the two-party analysis carries over).  x[i] = sum over q of shares[q][i] (mod 2^64); every party
+ * slices its own share; the p slices are added on XOR shares by a tree of two-operand adder circuits (neighbours
+ * (0,1), (2,3), ... level by level); sign, B2A, 1 - sign and the Beaver multiply as for two parties, every triple
+ * shared p ways, party 0 adding the public terms:
+ *   hb_drelu_mp: sum over q of outs[q][i] = 1 - MSB_w((u_0 + ... + u_{p-1}) mod 2^w),  u_q = (shares[q][i] >> k) mod 2^w
+ *   hb_relu_mp : sum over q of outs[q][i] = x[i] * that value.
+ * Dealer layout: an AND gate owns 3p-1 words a_0..a_{p-1} b_0..b_{p-1} c_0..c_{p-2}; gate t of adder s (adders in
+ * evaluation order) starts at word (s(1+2R) + t)(3p-1) of its group; a group owns (p-1)(1+2R)(3p-1) + 1 words, the
+ * last one holding the B2A bits (bit p*j + q: party q, lane j), so a group has L = min(floor(64/w), floor(64/p))
+ * elements; element i owns the 4p-2 arithmetic words rA_0..rA_{p-2} | a_0..a_{p-1} | b_0..b_{p-1} | c_0..c_{p-2}.
+ * With parties == 2 the calls are hb_drelu / hb_relu bit for bit.
+ *
+ * shares, outs: HOST arrays of `parties` DEVICE pointers (n int64 each, same rules as hb_relu: 8-byte aligned, an
+ * output may be exactly one of the inputs, no other overlap).  parties: 2, 3 or 4 (HB_EINVAL otherwise).
+ * opened_bits receives what ONE party sends to ONE other party: n * ((p-1) * 2w(1+2R) + 1) (+ 128 n for ReLU).
+ */
+#define HB_MAX_PARTIES 4
+HB_API int hb_drelu_mp(const int64_t *const *shares, int parties, size_t n, int k, int m, uint64_t seed,
+                       int64_t *const *outs, uint64_t *opened_bits, void *stream);
+HB_API int hb_relu_mp(const int64_t *const *shares, int parties, size_t n, int k, int m, uint64_t seed,
+                      int64_t *const *outs, uint64_t *opened_bits, void *stream);
+HB_API uint64_t hb_opened_bits_mp(int relu, int parties, int k, int m, size_t n);   /* 0 for invalid arguments */
+
+/*
  * Party-faithful ReLU: the same protocol and dealer material as hb_relu, but every opening goes through
  * memory the way it would go over the link between two GPUs (Sec. 2.2: each AND, the B2A and the multiply
  * open masked values; Sec. 4.2: the w-bit fields are packed into 64-bit words before each communication).

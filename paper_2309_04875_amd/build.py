@@ -27,6 +27,8 @@ HIPCC_FLAGS = [
 
 MODES = (0, 1, 2, 3, 4)                                 # DReLU, ReLU, sign shares; DReLU, ReLU on the shared-mask layout
 WIDTH_RANGES = ((1, 16), (17, 32), (33, 48), (49, 64))
+MP_PARTIES = (3, 4)                                     # multi-party kernels (two parties: the kernels above)
+MP_WIDTH_RANGES = ((1, 8), (9, 16), (17, 32), (33, 48), (49, 64))
 
 
 def _hipcc():
@@ -53,6 +55,11 @@ def build(verbose: bool = False, jobs: int = 0) -> str:
                 units.append((os.path.join(CSRC, "hb_launch_part.hip"),
                               os.path.join(work, "part_m%d_w%d.o" % (mode, lo)),
                               [("HB_PART_MODE", mode), ("HB_PART_LO", lo), ("HB_PART_HI", hi)]))
+        for parties in MP_PARTIES:
+            for lo, hi in MP_WIDTH_RANGES:
+                units.append((os.path.join(CSRC, "hb_mp_part.hip"),
+                              os.path.join(work, "mp_p%d_w%d.o" % (parties, lo)),
+                              [("HB_PART_PARTIES", parties), ("HB_PART_LO", lo), ("HB_PART_HI", hi)]))
         with ThreadPoolExecutor(max_workers=jobs) as pool:
             for out in pool.map(_compile, units):
                 if verbose and out.strip():

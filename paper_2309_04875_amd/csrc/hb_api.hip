@@ -13,6 +13,7 @@
 #include "hb_float.hpp"
 #include "hb_kernels.hpp"
 #include "hb_launch.hpp"
+#include "hb_multiparty.hpp"
 #include "hb_party.hpp"
 
 namespace {
@@ -168,6 +169,46 @@ int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k,
         if (e != hipSuccess) return fail_hip(e, "kernel launch");
     }
     if (opened_bits) *opened_bits = bits;
+    return HB_OK;
+}
+
+// DReLU / ReLU among `parties` parties.  shares / outs: host arrays of `parties` device pointers.
+int run_mp(int op, const int64_t *const *shares, int parties, size_t n, int k, int m, uint64_t seed,
+           int64_t *const *outs, uint64_t *opened_bits, void *stream)
+{
+    if (parties < 2 || parties > hb::kMaxParties) return HB_EINVAL;
+    if (shares == nullptr || outs == nullptr) return HB_EINVAL;
+    if (parties == 2) return run(op, shares[0], shares[1], n, k, m, seed, outs[0], outs[1], opened_bits, stream);
+    if (!valid_slice(k, m)) return HB_EINVAL;
+    const void *ptrs[2 * hb::kMaxParties];
+    for (int q = 0; q < parties; ++q) {
+        ptrs[q] = shares[q];
+        ptrs[parties + q] = outs[q];
+    }
+    const int st = check_common(ptrs, 2 * parties, n);
+    if (st != HB_OK) return st;
+    if (n > 0) {
+        // an output may coincide with an input; every other overlap is refused
+        for (int q = 0; q < parties; ++q) {
+            const Range out = range_of(outs[q], n);
+            for (int t = 0; t < parties; ++t) {
+                const Range in = range_of(shares[t], n);
+                if (!(same(out, in) || disjoint(out, in))) return HB_EINVAL;
+                if (t != q && !disjoint(out, range_of(outs[t], n))) return HB_EINVAL;
+            }
+        }
+        hb::MpPointers ptr = {};
+        for (int q = 0; q < parties; ++q) {
+            ptr.x[q] = (const uint64_t *)shares[q];
+            ptr.o[q] = (uint64_t *)outs[q];
+        }
+        const hb::MpLauncher f = hb::launcher_table().mp[parties - 3][op][m - k - 1];
+        if (f == nullptr) return fail_hip(hipErrorInvalidDeviceFunction, "no kernel was built for this slice width");
+        const hipError_t e = f(ptr, (uint64_t)n, k, hb::stream_word(seed, 0), hb::stream_word(seed, 1),
+                               all_aligned16(ptrs, 2 * parties), (hipStream_t)stream);
+        if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    }
+    if (opened_bits) *opened_bits = hb_opened_bits_mp(op == hb::kRelu, parties, k, m, n);
     return HB_OK;
 }
 
@@ -359,6 +400,18 @@ int hb_drelu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64
     const int mode = mode_on(hb::kDrelu, dealer);
     if (mode < 0) return HB_EINVAL;
     return run_batch(mode, tensors, count, opened_bits, stream);
+}
+
+int hb_drelu_mp(const int64_t *const *shares, int parties, size_t n, int k, int m, uint64_t seed,
+                int64_t *const *outs, uint64_t *opened_bits, void *stream)
+{
+    return run_mp(hb::kDrelu, shares, parties, n, k, m, seed, outs, opened_bits, stream);
+}
+
+int hb_relu_mp(const int64_t *const *shares, int parties, size_t n, int k, int m, uint64_t seed,
+               int64_t *const *outs, uint64_t *opened_bits, void *stream)
+{
+    return run_mp(hb::kRelu, shares, parties, n, k, m, seed, outs, opened_bits, stream);
 }
 
 size_t hb_party_wire_words(size_t n, int k, int m)
@@ -609,6 +662,14 @@ uint64_t hb_opened_bits_ex(int relu, int k, int m, size_t n, int dealer)
     const uint64_t per_round = dealer == HB_DEALER_SHARED_MASK ? 3 * w : 4 * w;
     const uint64_t per = 2 * w + per_round * R + 1 + (relu ? 128 : 0);
     return (uint64_t)n * per;
+}
+
+uint64_t hb_opened_bits_mp(int relu, int parties, int k, int m, size_t n)
+{
+    if (!valid_slice(k, m) || parties < 2 || parties > hb::kMaxParties) return 0;
+    const uint64_t w = (uint64_t)(m - k), R = (uint64_t)rounds_of((int)w);
+    // per link and direction: parties - 1 adders of 1 + 2R gates, each opening 2w bits
+    return (uint64_t)n * ((uint64_t)(parties - 1) * 2 * w * (1 + 2 * R) + 1 + (relu ? 128 : 0));
 }
 
 const char *hb_strerror(int status)

@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "hb_kernels.hpp"
+#include "hb_multiparty.hpp"
 
 namespace hb {
 
@@ -20,10 +21,15 @@ using BatchLauncher = hipError_t (*)(const BatchArgs &args, hipStream_t stream);
 using SimLauncher = hipError_t (*)(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t seedS,
                                    float *y, hipStream_t stream);
 
+// DReLU / ReLU among 3 or 4 parties (vec16: every buffer is 16-byte aligned).
+using MpLauncher = hipError_t (*)(const MpPointers &ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA, bool vec16,
+                                  hipStream_t stream);
+
 struct LauncherTable {
     GroupLauncher f[kModes][64];       // [mode][w - 1]
     BatchLauncher batch[kModes][64];   // null where the width has no tile kernel
     SimLauncher sim[64];               // null where the width has no tile kernel
+    MpLauncher mp[kMaxParties - 2][2][64];   // [parties - 3][kDrelu | kRelu][w - 1]
 };
 
 LauncherTable &launcher_table();

@@ -17,6 +17,7 @@ BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accountin
 EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_eco_scan", "hb_eco_choose",
            "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
            "hb_drelu_ex", "hb_relu_ex", "hb_relu_batch_ex", "hb_drelu_batch_ex",
+           "hb_drelu_mp", "hb_relu_mp", "hb_opened_bits_mp",
            "hb_tensor_seed",
            "hb_opened_bits", "hb_opened_bits_ex", "hb_strerror", "hb_last_hip_error")
 
@@ -65,6 +66,12 @@ def load():
         f.argtypes = [ctypes.POINTER(hb_tensor), sz, ci, u64p, vp]
     lib.hb_opened_bits_ex.restype = u64
     lib.hb_opened_bits_ex.argtypes = [ci, ci, ci, sz, ci]
+    for name in ("hb_drelu_mp", "hb_relu_mp"):
+        f = getattr(lib, name)
+        f.restype = ci
+        f.argtypes = [ctypes.POINTER(vp), ci, sz, ci, ci, u64, ctypes.POINTER(vp), u64p, vp]
+    lib.hb_opened_bits_mp.restype = u64
+    lib.hb_opened_bits_mp.argtypes = [ci, ci, ci, ci, sz]
     lib.hb_share_f32.restype = ci
     lib.hb_share_f32.argtypes = [vp, sz, u64, vp, vp, vp]
     lib.hb_reveal_f32.restype = ci
@@ -169,6 +176,38 @@ def hb_relu_ex(share0, share1, k, m, seed, dealer, out0=None, out1=None, stream=
 def hb_sign_shares(share0, share1, k, m, seed, out0=None, out1=None, stream=None):
     """XOR shares (0/1) of the sign bit after the adder circuit; returns (out0, out1, opened_bits)."""
     return _shares_call("hb_sign_shares", share0, share1, k, m, seed, out0, out1, stream)
+
+
+def _mp_call(name, shares, k, m, seed, outs, stream):
+    import torch
+    shares = list(shares)
+    if outs is None:
+        outs = [torch.empty_like(s) for s in shares]
+    outs = list(outs)
+    if len(outs) != len(shares):
+        raise ValueError("one output per party")
+    n = _tensor_args(*shares, *outs) if shares else 0
+    p = len(shares)
+    tab_in = (ctypes.c_void_p * max(p, 1))(*[s.data_ptr() for s in shares])
+    tab_out = (ctypes.c_void_p * max(p, 1))(*[o.data_ptr() for o in outs])
+    bits = ctypes.c_uint64(0)
+    _check(getattr(load(), name)(tab_in, p, n, int(k), int(m), int(seed) & (2**64 - 1), tab_out, ctypes.byref(bits),
+                                 _stream_handle(stream)))
+    return outs, int(bits.value)
+
+
+def hb_drelu_mp(shares, k, m, seed, outs=None, stream=None):
+    """DReLU among len(shares) parties; returns (list of output share tensors, opened bits per link)."""
+    return _mp_call("hb_drelu_mp", shares, k, m, seed, outs, stream)
+
+
+def hb_relu_mp(shares, k, m, seed, outs=None, stream=None):
+    """Approximate ReLU among len(shares) parties; returns (list of output share tensors, opened bits per link)."""
+    return _mp_call("hb_relu_mp", shares, k, m, seed, outs, stream)
+
+
+def hb_opened_bits_mp(relu, parties, k, m, n):
+    return int(load().hb_opened_bits_mp(int(bool(relu)), int(parties), int(k), int(m), int(n)))
 
 
 def make_batch(items):
