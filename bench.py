@@ -142,6 +142,17 @@ def main():
         extra["relu_w8_shared_mask_elems_per_s"] = n_total / (ms * 1e-3)
         extra["relu_w8_shared_mask_hbm_frac"] = BYTES_PER_ELEMENT * n_total / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         extra["relu_w8_shared_mask_opened_bits_per_element"] = hb.hb_opened_bits_ex(True, k, m, 1, hb.HB_DEALER_SHARED_MASK)
+        # three and four parties on the first tensor: 16 p bytes per element, (p - 1) adders
+        for parties in (3, 4):
+            more = [torch.randint(-(1 << 62), 1 << 62, (spec0.n,), dtype=torch.int64, device=dev)
+                    for _ in range(parties - 2)]
+            sh = [s0, s1] + more
+            outs = [o0, o1] + [torch.empty_like(t) for t in more]
+            ms = _time_launches(lambda: hb.hb_relu_mp(sh, k, m, seed0, outs), 40, torch)
+            extra["relu_mp%d_w8_elems_per_s" % parties] = spec0.n / (ms * 1e-3)
+            extra["relu_mp%d_w8_hbm_frac" % parties] = 16 * parties * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+            extra["relu_mp%d_w8_opened_bits_per_element_per_link" % parties] = hb.hb_opened_bits_mp(True, parties, k, m, 1)
+            del more, sh, outs
         ms = _time_launches(lambda: hb.hb_relu(s0, s1, 0, 64, seed0, o0, o1), 60, torch)
         extra["relu_w64_elems_per_s"] = spec0.n / (ms * 1e-3)
         extra["relu_w64_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
