@@ -191,9 +191,15 @@ def main():
             oracle.evaluate(a, b, sp.k, sp.m, sd, oracle.WHAT_RELU, threads=cores)
         c1 = time.perf_counter()
         n_cpu = sum(sp.n for (sp, _, _, _) in host)
+        sp, a, b, sd = host[0]
+        n_one = 1 << 23                          # one thread on the first 2^23 elements of tensor 0
+        d0 = time.perf_counter()
+        oracle.evaluate(a[:n_one], b[:n_one], sp.k, sp.m, sd, oracle.WHAT_RELU, threads=1)
+        d1 = time.perf_counter()
         cpu = {"value": n_cpu / (c1 - c0), "unit": "elements/s", "cores": cores, "kind": "oracle",
                "sample": "tensors 0-1 of the workload in full (%d elements), hb_relu at (12,20), "
-                         "element range split over %d threads" % (n_cpu, cores)}
+                         "element range split over %d threads" % (n_cpu, cores),
+               "one_core_value": n_one / (d1 - d0)}
 
     out = {
         "metric": "secret-shared ReLU elems/s at w=8 and w=64; % of HBM roofline",
