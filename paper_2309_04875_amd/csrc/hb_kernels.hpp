@@ -186,27 +186,33 @@ struct TileTraits {
 
 // ---- where a tile's element pairs come from and where the results go ----------------------------------------
 // Shares in, shares out: the library's normal boundary.
+// Element i = tile0 + e: tile0 (the tile's first element) is uniform over the wavefront, e is the lane's
+// 32-bit offset inside the tile, so an address is a scalar base plus a 32-bit vector offset.
 struct ShareIO {
     const uint64_t *x0, *x1;
     uint64_t *o0, *o1;
-    __device__ __forceinline__ void load_pair(uint64_t i, uint64_t n, U64x2 &a, U64x2 &b) const
+    template <bool FULL>
+    __device__ __forceinline__ void load_pair(uint64_t tile0, unsigned e, uint64_t n, U64x2 &a, U64x2 &b) const
     {
-        if (i + 1 < n) {
-            a = *reinterpret_cast<const U64x2 *>(x0 + i);
-            b = *reinterpret_cast<const U64x2 *>(x1 + i);
-        } else if (i < n) {
-            a.a = x0[i];
-            b.a = x1[i];
+        const uint64_t *t0 = x0 + tile0, *t1 = x1 + tile0;
+        if (FULL || tile0 + e + 1 < n) {
+            a = *reinterpret_cast<const U64x2 *>(t0 + e);
+            b = *reinterpret_cast<const U64x2 *>(t1 + e);
+        } else if (tile0 + e < n) {
+            a.a = t0[e];
+            b.a = t1[e];
         }
     }
-    __device__ __forceinline__ void store_pair(uint64_t i, uint64_t n, Pair r0, Pair r1) const
+    template <bool FULL>
+    __device__ __forceinline__ void store_pair(uint64_t tile0, unsigned e, uint64_t n, Pair r0, Pair r1) const
     {
-        if (i + 1 < n) {
-            *reinterpret_cast<U64x2 *>(o0 + i) = U64x2{r0.p0, r1.p0};
-            *reinterpret_cast<U64x2 *>(o1 + i) = U64x2{r0.p1, r1.p1};
-        } else if (i < n) {
-            o0[i] = r0.p0;
-            o1[i] = r0.p1;
+        uint64_t *t0 = o0 + tile0, *t1 = o1 + tile0;
+        if (FULL || tile0 + e + 1 < n) {
+            *reinterpret_cast<U64x2 *>(t0 + e) = U64x2{r0.p0, r1.p0};
+            *reinterpret_cast<U64x2 *>(t1 + e) = U64x2{r0.p1, r1.p1};
+        } else if (tile0 + e < n) {
+            t0[e] = r0.p0;
+            t1[e] = r0.p1;
         }
     }
 };
@@ -241,15 +247,18 @@ struct FloatIO {
     const float *x;
     float *y;
     uint64_t seedS;
-    __device__ __forceinline__ void load_pair(uint64_t i, uint64_t n, U64x2 &a, U64x2 &b) const
+    template <bool FULL>
+    __device__ __forceinline__ void load_pair(uint64_t tile0, unsigned e, uint64_t n, U64x2 &a, U64x2 &b) const
     {
+        const uint64_t i = tile0 + e;
+        const float *t = x + tile0;
         float f0 = 0.0f, f1 = 0.0f;
-        if (i + 1 < n) {
-            const F32x2 v = *reinterpret_cast<const F32x2 *>(x + i);
+        if (FULL || i + 1 < n) {
+            const F32x2 v = *reinterpret_cast<const F32x2 *>(t + e);
             f0 = v.a;
             f1 = v.b;
         } else if (i < n) {
-            f0 = x[i];
+            f0 = t[e];
         } else {
             return;
         }
@@ -259,20 +268,23 @@ struct FloatIO {
         b.a = encode_fixed16(f0) - a.a;
         b.b = encode_fixed16(f1) - a.b;
     }
-    __device__ __forceinline__ void store_pair(uint64_t i, uint64_t n, Pair r0, Pair r1) const
+    template <bool FULL>
+    __device__ __forceinline__ void store_pair(uint64_t tile0, unsigned e, uint64_t n, Pair r0, Pair r1) const
     {
-        if (i + 1 < n) {
-            *reinterpret_cast<F32x2 *>(y + i) = F32x2{decode_fixed16(r0.p0 + r0.p1), decode_fixed16(r1.p0 + r1.p1)};
-        } else if (i < n) {
-            y[i] = decode_fixed16(r0.p0 + r0.p1);
+        float *t = y + tile0;
+        if (FULL || tile0 + e + 1 < n) {
+            *reinterpret_cast<F32x2 *>(t + e) = F32x2{decode_fixed16(r0.p0 + r0.p1), decode_fixed16(r1.p0 + r1.p1)};
+        } else if (tile0 + e < n) {
+            t[e] = decode_fixed16(r0.p0 + r0.p1);
         }
     }
 };
 
-// Work of one wavefront on wave-tile `tile` of one tensor.  slice_lds / verdict: this wave's LDS.
-template <int W, int MODE, class IO>
-__device__ __forceinline__ void tile_body(const IO &io, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
-                                          uint64_t tile, int lane, unsigned char *slice_lds, U64x2 *verdict)
+// Work of one wavefront on wave-tile `tile` of one tensor.  slice_lds / verdict: this wave's LDS.  FULL: the
+// whole tile lies inside the tensor, so no access needs a bounds check (every tile but a tensor's last).
+template <int W, int MODE, bool FULL, class IO>
+__device__ __forceinline__ void tile_body_impl(const IO &io, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
+                                               uint64_t tile, int lane, unsigned char *slice_lds, U64x2 *verdict)
 {
     using T = TileTraits<W>;
     using S = Shape<W>;
@@ -289,8 +301,7 @@ __device__ __forceinline__ void tile_body(const IO &io, uint64_t n, int k, uint6
         xa[c] = U64x2{0, 0};
         xb[c] = U64x2{0, 0};
         if (e < T::kTile) {
-            const uint64_t i = tile0 + e;
-            io.load_pair(i, n, xa[c], xb[c]);
+            io.template load_pair<FULL>(tile0, (unsigned)e, n, xa[c], xb[c]);
             if constexpr (T::kPacked) {
                 // the pair's two fields of party 0 / party 1, already at their place relative to the pair
                 using Item = typename T::Item;
@@ -366,9 +377,27 @@ __device__ __forceinline__ void tile_body(const IO &io, uint64_t n, int k, uint6
                     r[h] = (op_of(MODE) == kDrelu) ? D : beaver_mul(Pair{h ? xa[c].b : xa[c].a, h ? xb[c].b : xb[c].a}, D, zA);
                 }
             }
-            io.store_pair(i, n, r[0], r[1]);
+            io.template store_pair<FULL>(tile0, (unsigned)e, n, r[0], r[1]);
         }
     }
+}
+
+// `tile` must be uniform over the wavefront (callers derive it from wave_index()).
+template <int W, int MODE, class IO>
+__device__ __forceinline__ void tile_body(const IO &io, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
+                                          uint64_t tile, int lane, unsigned char *slice_lds, U64x2 *verdict)
+{
+    if ((tile + 1) * TileTraits<W>::kTile <= n)
+        tile_body_impl<W, MODE, true>(io, n, k, seedB, seedA, tile, lane, slice_lds, verdict);
+    else
+        tile_body_impl<W, MODE, false>(io, n, k, seedB, seedA, tile, lane, slice_lds, verdict);
+}
+
+// The wavefront's number inside its workgroup, as a scalar: everything derived from it (tile number, tensor
+// descriptor, base addresses) then stays in scalar registers.
+__device__ __forceinline__ int wave_index()
+{
+    return __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
 }
 
 template <int W, int MODE>
@@ -379,7 +408,7 @@ tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t 
     using T = TileTraits<W>;
     __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][T::kSliceBytes];
     __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];     // per group: {sign shares, B2A dealer word}
-    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave, wv = wave_index();
     const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     if (tile * T::kTile >= n) return;        // whole wavefront beyond the tensor (uniform per wave)
     tile_body<W, MODE>(ShareIO{x0, x1, o0, o1}, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
@@ -410,7 +439,7 @@ tile_batch_kernel(const BatchArgs args)
     using T = TileTraits<W>;
     __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][T::kSliceBytes];
     __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];
-    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave, wv = wave_index();
     const uint64_t gt = (uint64_t)blockIdx.x * kWavesPerBlock + wv;          // wave-tile number over the whole batch
     if (gt >= args.tile_end[args.count - 1]) return;
     int ti = 0;
@@ -428,7 +457,7 @@ tile_sim_kernel(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seed
     using T = TileTraits<W>;
     __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][T::kSliceBytes];
     __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];
-    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave, wv = wave_index();
     const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     if (tile * T::kTile >= n) return;
     tile_body<W, kRelu>(FloatIO{x, y, seedS}, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);

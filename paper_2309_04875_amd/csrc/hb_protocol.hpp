@@ -71,10 +71,28 @@ struct Pair {      // one value held as (party 0 share, party 1 share)
     uint64_t p0, p1;
 };
 
-// One Beaver AND on XOR-shared words.  zq is the generator state of the gate's first dealer word
-// (word a_0); the five words a_0 a_1 b_0 b_1 c_0 are consecutive outputs.  U is masked by a, V by b;
-// d and e are the opened words; party 0 takes the public d&e term.
-__device__ __forceinline__ Pair beaver_and(uint64_t zq, Pair U, Pair V)
+// ---- three-input bitwise operations (v_bitop3_b32, one instruction per 32-bit half) ----------------------------
+// The 8-bit truth table of a boolean function f(a, b, c), in the instruction's operand order.
+constexpr unsigned kTtXor3 = (0xF0 ^ 0xCC ^ 0xAA) & 0xFF;              // a ^ b ^ c
+constexpr unsigned kTtXorAnd = (0xF0 ^ (0xCC & 0xAA)) & 0xFF;          // a ^ (b & c)
+constexpr unsigned kTtAndXor = (0xF0 & (0xCC ^ 0xAA)) & 0xFF;          // a & (b ^ c)
+
+template <unsigned TT>
+__device__ __forceinline__ uint64_t bitop3(uint64_t a, uint64_t b, uint64_t c)
+{
+    const uint32_t lo = __builtin_amdgcn_bitop3_b32((uint32_t)a, (uint32_t)b, (uint32_t)c, TT);
+    const uint32_t hi = __builtin_amdgcn_bitop3_b32((uint32_t)(a >> 32), (uint32_t)(b >> 32), (uint32_t)(c >> 32), TT);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// One Beaver AND on XOR-shared words, Z = U & V, returned as acc ^ Z share by share (acc = {0, 0} for the
+// plain gate; the G-update of a prefix round passes the old G).  zq is the generator state of the gate's first
+// dealer word; the five words a_0 a_1 b_0 b_1 c_0 are consecutive outputs.  U is masked by a, V by b.
+// The gate sees U and V only through the two openings, and an opening is the XOR of what the two parties
+// send, (U_0 ^ a_0) ^ (U_1 ^ a_1) = (U_0 ^ U_1) ^ (a_0 ^ a_1); the caller passes Ux = U_0 ^ U_1 and
+// Vx = (V_0 ^ V_1) before the field mask `keep` that confines a shifted operand to its field (all ones when
+// the operand is not shifted).  Party 0 takes the public d & e term.
+__device__ __forceinline__ Pair beaver_and(uint64_t zq, uint64_t Ux, uint64_t Vx, uint64_t keep, Pair acc)
 {
     const uint64_t a0 = mix64(zq);
     const uint64_t a1 = mix64(zq + 1 * kGamma);
@@ -82,45 +100,49 @@ __device__ __forceinline__ Pair beaver_and(uint64_t zq, Pair U, Pair V)
     const uint64_t b1 = mix64(zq + 3 * kGamma);
     const uint64_t c0 = mix64(zq + 4 * kGamma);
     const uint64_t a = a0 ^ a1, b = b0 ^ b1;                    // the dealer's triple (a, b, a & b)
-    const uint64_t c1 = (a & b) ^ c0;                           // dealer completes the sharing of c
-    const uint64_t d = (U.p0 ^ U.p1) ^ a;                       // opened: XOR of what each party sends, U_p ^ a_p
-    const uint64_t e = (V.p0 ^ V.p1) ^ b;                       // opened: XOR of V_p ^ b_p
+    const uint64_t d = Ux ^ a;                                  // opened
+    const uint64_t e = bitop3<kTtXorAnd>(b, Vx, keep);          // opened: (Vx & keep) ^ b
     Pair Z;
-    Z.p0 = c0 ^ (d & (b0 ^ e)) ^ (e & a0);                      // = c0 ^ (d & b0) ^ (e & a0) ^ (d & e)
-    Z.p1 = c1 ^ (d & b1) ^ (e & a1);
+    // party 0: acc ^ c_0 ^ (e & a_0) ^ (d & (b_0 ^ e))    [= c_0 ^ (d & b_0) ^ (e & a_0) ^ (d & e)]
+    Z.p0 = bitop3<kTtXor3>(acc.p0, bitop3<kTtXorAnd>(c0, e, a0), bitop3<kTtAndXor>(d, b0, e));
+    // party 1: acc ^ c_1 ^ (d & b_1) ^ (e & a_1), the dealer having completed c_1 = (a & b) ^ c_0
+    const uint64_t c1 = bitop3<kTtXorAnd>(c0, a, b);
+    Z.p1 = bitop3<kTtXorAnd>(bitop3<kTtXorAnd>(acc.p1 ^ c1, d, b1), e, a1);
     return Z;
 }
 
 // The two Beaver ANDs of a prefix round when one mask serves their common first operand U: T = U & V, Q = U & Y.
 // zr is the generator state of the round's first word; the eight words a_0 a_1 | b_0 b_1 c_0 (for V) |
-// b_0 b_1 c_0 (for Y) are consecutive outputs.  d = U ^ a is opened once.  With kSecond false only the first
-// gate is evaluated and its three last words are never drawn.
+// b_0 b_1 c_0 (for Y) are consecutive outputs.  d = U ^ a is opened once.  Operands and `keep` as in beaver_and;
+// T comes back XORed onto accT.  With kSecond false only the first gate is evaluated and its three last words are
+// never drawn.
 template <bool kSecond>
-__device__ __forceinline__ void beaver_and_shared(uint64_t zr, Pair U, Pair V, Pair Y, Pair &T, Pair &Q)
+__device__ __forceinline__ void beaver_and_shared(uint64_t zr, uint64_t Ux, uint64_t Vx, uint64_t Yx, uint64_t keep,
+                                                  Pair accT, Pair &T, Pair &Q)
 {
     const uint64_t a0 = mix64(zr);
     const uint64_t a1 = mix64(zr + 1 * kGamma);
     const uint64_t a = a0 ^ a1;
-    const uint64_t d = (U.p0 ^ U.p1) ^ a;
+    const uint64_t d = Ux ^ a;
     {
         const uint64_t b0 = mix64(zr + 2 * kGamma);
         const uint64_t b1 = mix64(zr + 3 * kGamma);
         const uint64_t c0 = mix64(zr + 4 * kGamma);
         const uint64_t b = b0 ^ b1;
-        const uint64_t c1 = (a & b) ^ c0;
-        const uint64_t e = (V.p0 ^ V.p1) ^ b;
-        T.p0 = c0 ^ (d & (b0 ^ e)) ^ (e & a0);
-        T.p1 = c1 ^ (d & b1) ^ (e & a1);
+        const uint64_t e = bitop3<kTtXorAnd>(b, Vx, keep);
+        T.p0 = bitop3<kTtXor3>(accT.p0, bitop3<kTtXorAnd>(c0, e, a0), bitop3<kTtAndXor>(d, b0, e));
+        const uint64_t c1 = bitop3<kTtXorAnd>(c0, a, b);
+        T.p1 = bitop3<kTtXorAnd>(bitop3<kTtXorAnd>(accT.p1 ^ c1, d, b1), e, a1);
     }
     if (kSecond) {
         const uint64_t b0 = mix64(zr + 5 * kGamma);
         const uint64_t b1 = mix64(zr + 6 * kGamma);
         const uint64_t c0 = mix64(zr + 7 * kGamma);
         const uint64_t b = b0 ^ b1;
-        const uint64_t c1 = (a & b) ^ c0;
-        const uint64_t e = (Y.p0 ^ Y.p1) ^ b;
-        Q.p0 = c0 ^ (d & (b0 ^ e)) ^ (e & a0);
-        Q.p1 = c1 ^ (d & b1) ^ (e & a1);
+        const uint64_t e = bitop3<kTtXorAnd>(b, Yx, keep);
+        Q.p0 = bitop3<kTtXorAnd>(c0, e, a0) ^ bitop3<kTtAndXor>(d, b0, e);
+        const uint64_t c1 = bitop3<kTtXorAnd>(c0, a, b);
+        Q.p1 = bitop3<kTtXorAnd>(bitop3<kTtXorAnd>(c1, d, b1), e, a1);
     }
 }
 
@@ -137,26 +159,24 @@ __device__ __forceinline__ Pair a2b_sum(uint64_t u0, uint64_t u1, uint64_t zg)
     const Pair X{u0, 0}, Y{0, u1};
     Pair P{X.p0 ^ Y.p0, X.p1 ^ Y.p1};
     const Pair Sum = P;
-    Pair G = beaver_and(zg, X, Y);
+    Pair G = beaver_and(zg, X.p0 ^ X.p1, Y.p0 ^ Y.p1, ~0ull, Pair{0, 0});
 #pragma unroll
     for (int r = 0; r < S::R; ++r) {
         const int s = 1 << r;
         const uint64_t keep = S::keep(s);
-        const Pair Gs{(G.p0 << s) & keep, (G.p1 << s) & keep};
-        const Pair Ps{(P.p0 << s) & keep, (P.p1 << s) & keep};
+        // shifting is linear: the XOR of the parties' shifted shares is the shifted XOR of their shares
+        const uint64_t Px = P.p0 ^ P.p1;
+        const uint64_t Gsx = (G.p0 ^ G.p1) << s, Psx = Px << s;
         const uint64_t zr = zg + (uint64_t)S::round_word(SHARED, r) * kGamma;
-        Pair T;
         if (SHARED) {
             Pair Pn = P;
-            if (r + 1 < S::R) beaver_and_shared<true>(zr, P, Gs, Ps, T, Pn);
-            else beaver_and_shared<false>(zr, P, Gs, Ps, T, Pn);
+            if (r + 1 < S::R) beaver_and_shared<true>(zr, Px, Gsx, Psx, keep, G, G, Pn);
+            else beaver_and_shared<false>(zr, Px, Gsx, Psx, keep, G, G, Pn);
             P = Pn;
         } else {
-            T = beaver_and(zr, P, Gs);
-            if (r + 1 < S::R) P = beaver_and(zr + 5 * kGamma, P, Ps);
+            G = beaver_and(zr, Px, Gsx, keep, G);
+            if (r + 1 < S::R) P = beaver_and(zr + 5 * kGamma, Px, Psx, keep, Pair{0, 0});
         }
-        G.p0 ^= T.p0;
-        G.p1 ^= T.p1;
     }
     const uint64_t keep1 = S::keep(1);
     return Pair{Sum.p0 ^ ((G.p0 << 1) & keep1), Sum.p1 ^ ((G.p1 << 1) & keep1)};
@@ -184,9 +204,10 @@ __device__ __forceinline__ Pair beaver_mul(Pair x, Pair D, uint64_t zA)
     const uint64_t b0 = mix64(zA + 3 * kGamma);
     const uint64_t b1 = mix64(zA + 4 * kGamma);
     const uint64_t c0 = mix64(zA + 5 * kGamma);
-    const uint64_t c1 = (a0 + a1) * (b0 + b1) - c0;               // dealer completes the triple
-    const uint64_t eps = (x.p0 - a0) + (x.p1 - a1);               // opened
-    const uint64_t del = (D.p0 - b0) + (D.p1 - b1);               // opened
+    const uint64_t a = a0 + a1, b = b0 + b1;                      // the dealer's triple (a, b, a * b)
+    const uint64_t c1 = a * b - c0;                               // dealer completes the sharing of c
+    const uint64_t eps = (x.p0 + x.p1) - a;                       // opened: (x_0 - a_0) + (x_1 - a_1)
+    const uint64_t del = (D.p0 - b0) + (D.p1 - b1);               // opened: each party's message, summed
     Pair out;
     out.p0 = c0 + eps * (b0 + del) + del * a0;                    // = c0 + eps*b0 + del*a0 + eps*del
     out.p1 = c1 + eps * b1 + del * a1;
