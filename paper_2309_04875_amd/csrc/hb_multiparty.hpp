@@ -45,33 +45,34 @@ struct MpShape {
     static constexpr int kArithWords = 4 * P - 2;
 };
 
-// Beaver AND among P parties; zq = generator state of the gate's first dealer word.
+// Beaver AND among P parties, returned XORed onto acc share by share; zq = generator state of the gate's first
+// dealer word.  As in the two-party gate the operands enter only through the openings: Ux = XOR over the parties
+// of U_q, Vx = XOR of V_q before the field mask `keep` of a shifted operand.
 template <int P>
-__device__ __forceinline__ Shares<P> mp_and(uint64_t zq, const Shares<P> &U, const Shares<P> &V)
+__device__ __forceinline__ Shares<P> mp_and(uint64_t zq, uint64_t Ux, uint64_t Vx, uint64_t keep, const Shares<P> &acc)
 {
     uint64_t a[P], b[P], c[P];
-    uint64_t as = 0, bs = 0, cs = 0, d = 0, e = 0;
+    uint64_t as = 0, bs = 0, cs = 0;
 #pragma unroll
     for (int q = 0; q < P; ++q) {
         a[q] = mix64(zq + (uint64_t)q * kGamma);
         b[q] = mix64(zq + (uint64_t)(P + q) * kGamma);
         as ^= a[q];
         bs ^= b[q];
-        d ^= U.v[q];
-        e ^= V.v[q];
     }
 #pragma unroll
     for (int q = 0; q < P - 1; ++q) {
         c[q] = mix64(zq + (uint64_t)(2 * P + q) * kGamma);
         cs ^= c[q];
     }
-    c[P - 1] = (as & bs) ^ cs;      // the dealer completes the sharing of c = a & b
-    d ^= as;                        // opened: XOR over the parties of U_q ^ a_q
-    e ^= bs;                        // opened: XOR over the parties of V_q ^ b_q
+    c[P - 1] = bitop3<kTtXorAnd>(cs, as, bs);               // the dealer completes the sharing of c = a & b
+    const uint64_t d = Ux ^ as;                             // opened: XOR over the parties of U_q ^ a_q
+    const uint64_t e = bitop3<kTtXorAnd>(bs, Vx, keep);     // opened: XOR over the parties of V_q ^ b_q
     Shares<P> Z;
+    // party 0 takes the public d & e term: c_0 ^ (d & b_0) ^ (e & a_0) ^ (d & e)
+    Z.v[0] = bitop3<kTtXor3>(acc.v[0], bitop3<kTtXorAnd>(c[0], e, a[0]), bitop3<kTtAndXor>(d, b[0], e));
 #pragma unroll
-    for (int q = 0; q < P; ++q) Z.v[q] = c[q] ^ (d & b[q]) ^ (e & a[q]);
-    Z.v[0] ^= d & e;
+    for (int q = 1; q < P; ++q) Z.v[q] = bitop3<kTtXorAnd>(bitop3<kTtXorAnd>(acc.v[q] ^ c[q], d, b[q]), e, a[q]);
     return Z;
 }
 
@@ -82,24 +83,31 @@ __device__ __forceinline__ Shares<P> mp_add(uint64_t za, const Shares<P> &X, con
 {
     using S = Shape<W>;
     using M = MpShape<W, P>;
-    Shares<P> Pw, Sum;
+    Shares<P> Pw, Sum, zero;
+    uint64_t Xx = 0, Yx = 0;
 #pragma unroll
-    for (int q = 0; q < P; ++q) Pw.v[q] = Sum.v[q] = X.v[q] ^ Y.v[q];
-    Shares<P> G = mp_and<P>(za, X, Y);
+    for (int q = 0; q < P; ++q) {
+        Pw.v[q] = Sum.v[q] = X.v[q] ^ Y.v[q];
+        zero.v[q] = 0;
+        Xx ^= X.v[q];
+        Yx ^= Y.v[q];
+    }
+    Shares<P> G = mp_and<P>(za, Xx, Yx, ~0ull, zero);
 #pragma unroll
     for (int r = 0; r < S::R; ++r) {
         const int s = 1 << r;
         const uint64_t keep = S::keep(s);
-        Shares<P> Gs, Ps;
+        // shifting is linear: the XOR of the parties' shifted shares is the shifted XOR of their shares
+        uint64_t Gx = 0, Px = 0;
 #pragma unroll
         for (int q = 0; q < P; ++q) {
-            Gs.v[q] = (G.v[q] << s) & keep;
-            Ps.v[q] = (Pw.v[q] << s) & keep;
+            Gx ^= G.v[q];
+            Px ^= Pw.v[q];
         }
-        const Shares<P> T = mp_and<P>(za + (uint64_t)((1 + 2 * r) * M::kGateWords) * kGamma, Pw, Gs);
-        if (r + 1 < S::R) Pw = mp_and<P>(za + (uint64_t)((2 + 2 * r) * M::kGateWords) * kGamma, Pw, Ps);
-#pragma unroll
-        for (int q = 0; q < P; ++q) G.v[q] ^= T.v[q];
+        // one gate's dealer words at a time (not_before): 3P - 1 live words instead of the whole adder's
+        G = mp_and<P>(not_before(za + (uint64_t)((1 + 2 * r) * M::kGateWords) * kGamma, Gx), Px, Gx << s, keep, G);
+        if (r + 1 < S::R)
+            Pw = mp_and<P>(not_before(za + (uint64_t)((2 + 2 * r) * M::kGateWords) * kGamma, G.v[0]), Px, Px << s, keep, zero);
     }
     const uint64_t keep1 = S::keep(1);
     Shares<P> out;
@@ -155,7 +163,7 @@ __device__ __forceinline__ Shares<P> mp_finish(uint32_t sign, uint32_t rho, cons
 
     const uint64_t zM = zA + (uint64_t)(P - 1) * kGamma;
     uint64_t a[P], b[P], c[P];
-    uint64_t as = 0, bs = 0, cs = 0, xs = 0, ds = 0;
+    uint64_t as = 0, bs = 0, cs = 0, xs = 0, del = 0;
 #pragma unroll
     for (int q = 0; q < P; ++q) {
         a[q] = mix64(zM + (uint64_t)q * kGamma);
@@ -163,20 +171,21 @@ __device__ __forceinline__ Shares<P> mp_finish(uint32_t sign, uint32_t rho, cons
         as += a[q];
         bs += b[q];
         xs += x.v[q];
-        ds += D.v[q];
+        del += D.v[q] - b[q];                // opened: each party's message D_q - b_q, summed
     }
 #pragma unroll
     for (int q = 0; q < P - 1; ++q) {
         c[q] = mix64(zM + (uint64_t)(2 * P + q) * kGamma);
         cs += c[q];
     }
-    c[P - 1] = as * bs - cs;                 // the dealer completes the triple
     const uint64_t eps = xs - as;            // opened: sum over the parties of x_q - a_q
-    const uint64_t del = ds - bs;            // opened: sum over the parties of D_q - b_q
     Shares<P> out;
+    // party 0 takes the public term: c_0 + eps * b_0 + del * a_0 + eps * del
+    out.v[0] = sum_of_products(c[0], eps, b[0] + del, del, a[0]);
 #pragma unroll
-    for (int q = 0; q < P; ++q) out.v[q] = c[q] + eps * b[q] + del * a[q];
-    out.v[0] += eps * del;
+    for (int q = 1; q < P - 1; ++q) out.v[q] = sum_of_products(c[q], eps, b[q], del, a[q]);
+    // the last party's c completes the triple: c_{P-1} = a * b - (c_0 + ... + c_{P-2})
+    out.v[P - 1] = sum_of_products(0 - cs, as, bs, eps, b[P - 1], del, a[P - 1]);
     return out;
 }
 
@@ -241,41 +250,37 @@ struct MpTileTraits {
     static constexpr int kSliceBytes = ((kTile * (int)sizeof(Entry) + 15) / 16) * 16;   // per party
 };
 
-template <int W, int P, int MODE>
-__global__ void __launch_bounds__(kBlock)
-mp_tile_kernel(const MpPointers ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA)
+// Work of one wavefront on wave-tile `tile` (uniform over the wavefront).  FULL: the whole tile lies inside the
+// tensor, so no access needs a bounds check (every tile but the last).
+template <int W, int P, int MODE, bool FULL>
+__device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
+                                             uint64_t tile, int lane, unsigned char (*slice_lds)[MpTileTraits<W, P>::kSliceBytes],
+                                             U64x2 *verdict)
 {
     using S = Shape<W>;
     using M = MpShape<W, P>;
     using T = MpTileTraits<W, P>;
     using Entry = typename T::Entry;
     constexpr int L = T::L;
-    static_assert(T::kSupported, "tile kernel needs 4 <= W <= 32");
-    __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][P][T::kSliceBytes];
-    __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];
-    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-    const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     const uint64_t tile0 = tile * T::kTile;
-    if (tile0 >= n) return;                  // whole wavefront beyond the tensor (uniform per wave)
-    U64x2 *verdict = verdict_all[wv];
 
     // ---- owners: load, slice, deposit
     U64x2 xs[P][T::kPairs];
 #pragma unroll
     for (int c = 0; c < T::kPairs; ++c) {
-        const int e = 2 * (c * kWave + lane);
+        const unsigned e = 2 * (c * kWave + lane);
 #pragma unroll
         for (int q = 0; q < P; ++q) xs[q][c] = U64x2{0, 0};
-        if (e < T::kTile) {
-            const uint64_t i = tile0 + e;
+        if (e < (unsigned)T::kTile) {
 #pragma unroll
             for (int q = 0; q < P; ++q) {
-                if (i + 1 < n) {
-                    xs[q][c] = *reinterpret_cast<const U64x2 *>(ptr.x[q] + i);
-                } else if (i < n) {
-                    xs[q][c].a = ptr.x[q][i];
+                const uint64_t *t = ptr.x[q] + tile0;       // scalar base, 32-bit lane offset
+                if (FULL || tile0 + e + 1 < n) {
+                    xs[q][c] = *reinterpret_cast<const U64x2 *>(t + e);
+                } else if (tile0 + e < n) {
+                    xs[q][c].a = t[e];
                 }
-                Entry *sl = reinterpret_cast<Entry *>(slices_all[wv][q]);
+                Entry *sl = reinterpret_cast<Entry *>(slice_lds[q]);
                 sl[e] = (Entry)((xs[q][c].a >> k) & S::kField);
                 sl[e + 1] = (Entry)((xs[q][c].b >> k) & S::kField);
             }
@@ -288,9 +293,9 @@ mp_tile_kernel(const MpPointers ptr, uint64_t n, int k, uint64_t seedB, uint64_t
 #pragma unroll
     for (int q = 0; q < P; ++q) {
         if constexpr (T::kWordIsPacked) {
-            u[q] = reinterpret_cast<const uint64_t *>(slices_all[wv][q])[lane];
+            u[q] = reinterpret_cast<const uint64_t *>(slice_lds[q])[lane];
         } else {
-            const Entry *sl = reinterpret_cast<const Entry *>(slices_all[wv][q]);
+            const Entry *sl = reinterpret_cast<const Entry *>(slice_lds[q]);
             u[q] = 0;
 #pragma unroll
             for (int j = 0; j < L; ++j) u[q] |= (uint64_t)sl[lane * L + j] << (j * W);
@@ -312,9 +317,8 @@ mp_tile_kernel(const MpPointers ptr, uint64_t n, int k, uint64_t seedB, uint64_t
     const uint64_t zA0 = seedA + ((uint64_t)M::kArithWords * (tile0 + 2 * (uint64_t)lane) + 1) * kGamma;
 #pragma unroll
     for (int c = 0; c < T::kPairs; ++c) {
-        const int e = 2 * (c * kWave + lane);
-        if (e < T::kTile) {
-            const uint64_t i = tile0 + e;
+        const unsigned e = 2 * (c * kWave + lane);
+        if (e < (unsigned)T::kTile) {
             const int grp0 = e / L, j0 = e - grp0 * L;
             const U64x2 v0 = verdict[grp0];
             const bool split = (L % 2 != 0) && (j0 == L - 1);     // the pair straddles two groups (odd L only)
@@ -334,14 +338,32 @@ mp_tile_kernel(const MpPointers ptr, uint64_t n, int k, uint64_t seedB, uint64_t
             }
 #pragma unroll
             for (int q = 0; q < P; ++q) {
-                if (i + 1 < n) {
-                    *reinterpret_cast<U64x2 *>(ptr.o[q] + i) = U64x2{r[0].v[q], r[1].v[q]};
-                } else if (i < n) {
-                    ptr.o[q][i] = r[0].v[q];
+                uint64_t *t = ptr.o[q] + tile0;
+                if (FULL || tile0 + e + 1 < n) {
+                    *reinterpret_cast<U64x2 *>(t + e) = U64x2{r[0].v[q], r[1].v[q]};
+                } else if (tile0 + e < n) {
+                    t[e] = r[0].v[q];
                 }
             }
         }
     }
+}
+
+template <int W, int P, int MODE>
+__global__ void __launch_bounds__(kBlock)
+mp_tile_kernel(const MpPointers ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA)
+{
+    using T = MpTileTraits<W, P>;
+    static_assert(T::kSupported, "tile kernel needs 4 <= W <= 32");
+    __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][P][T::kSliceBytes];
+    __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];
+    const int lane = threadIdx.x % kWave, wv = wave_index();
+    const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
+    if (tile * T::kTile >= n) return;        // whole wavefront beyond the tensor
+    if ((tile + 1) * T::kTile <= n)
+        mp_tile_body<W, P, MODE, true>(ptr, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+    else
+        mp_tile_body<W, P, MODE, false>(ptr, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 }  // namespace hb

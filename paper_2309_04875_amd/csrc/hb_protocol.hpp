@@ -71,6 +71,16 @@ struct Pair {      // one value held as (party 0 share, party 1 share)
     uint64_t p0, p1;
 };
 
+// Returns z, which the compiler may not compute before `after` is known.  Dealer words depend only on the group
+// or element number, so the scheduler would otherwise generate those of every gate ahead of the circuit and
+// hold them all in registers; tying a gate's generator state to the previous gate's result keeps their live
+// ranges one gate long.  Emits no instruction.
+__device__ __forceinline__ uint64_t not_before(uint64_t z, uint64_t after)
+{
+    asm("" : "+v"(z) : "v"(after));
+    return z;
+}
+
 // ---- three-input bitwise operations (v_bitop3_b32, one instruction per 32-bit half) ----------------------------
 // The 8-bit truth table of a boolean function f(a, b, c), in the instruction's operand order.
 constexpr unsigned kTtXor3 = (0xF0 ^ 0xCC ^ 0xAA) & 0xFF;              // a ^ b ^ c
@@ -167,7 +177,7 @@ __device__ __forceinline__ Pair a2b_sum(uint64_t u0, uint64_t u1, uint64_t zg)
         // shifting is linear: the XOR of the parties' shifted shares is the shifted XOR of their shares
         const uint64_t Px = P.p0 ^ P.p1;
         const uint64_t Gsx = (G.p0 ^ G.p1) << s, Psx = Px << s;
-        const uint64_t zr = zg + (uint64_t)S::round_word(SHARED, r) * kGamma;
+        const uint64_t zr = not_before(zg + (uint64_t)S::round_word(SHARED, r) * kGamma, G.p0);
         if (SHARED) {
             Pair Pn = P;
             if (r + 1 < S::R) beaver_and_shared<true>(zr, Px, Gsx, Psx, keep, G, G, Pn);
@@ -196,6 +206,49 @@ __device__ __forceinline__ Pair b2a_drelu(Pair sign, Pair rho, uint64_t zA)
     return Pair{1 - beta0, 0 - beta1};
 }
 
+// ---- products on Z_2^64 out of 32-bit halves --------------------------------------------------------------------
+// x * y mod 2^64 = lo(x) lo(y) + 2^32 (lo(x) hi(y) + hi(x) lo(y)).  v_mad_u64_u32 (32 x 32 + 64 -> 64) adds while it
+// multiplies, so a sum of products costs one instruction per 32 x 32 product plus one final add when the cross
+// products are accumulated in a 64-bit register of their own, of which only the low half is used.  held() keeps
+// that register whole: without it the compiler narrows the chain to 32-bit multiplies followed by separate adds.
+__device__ __forceinline__ uint64_t held(uint64_t v)
+{
+    asm("" : "+v"(v));
+    return v;
+}
+__device__ __forceinline__ uint64_t lo32(uint64_t v) { return (uint32_t)v; }
+__device__ __forceinline__ uint64_t hi32(uint64_t v) { return v >> 32; }
+// low + 2^32 * cross, touching only the high half of `low`
+__device__ __forceinline__ uint64_t add_to_high(uint64_t low, uint64_t cross)
+{
+    uint32_t h = (uint32_t)(low >> 32) + (uint32_t)cross;
+    asm("" : "+v"(h));      // keeps the sum a 32-bit add (otherwise it is widened to a 64-bit add of {0, cross})
+    return ((uint64_t)h << 32) | (uint32_t)low;
+}
+
+// acc + x * y (+ u * v) (+ s * t)  mod 2^64
+__device__ __forceinline__ uint64_t sum_of_products(uint64_t acc, uint64_t x, uint64_t y, uint64_t u, uint64_t v)
+{
+    uint64_t cross = held(lo32(x) * hi32(y));
+    cross = held(hi32(x) * lo32(y) + cross);
+    cross = held(lo32(u) * hi32(v) + cross);
+    cross = held(hi32(u) * lo32(v) + cross);
+    const uint64_t low = lo32(u) * lo32(v) + (lo32(x) * lo32(y) + acc);
+    return add_to_high(held(low), cross);
+}
+__device__ __forceinline__ uint64_t sum_of_products(uint64_t acc, uint64_t x, uint64_t y, uint64_t u, uint64_t v,
+                                                    uint64_t s, uint64_t t)
+{
+    uint64_t cross = held(lo32(x) * hi32(y));
+    cross = held(hi32(x) * lo32(y) + cross);
+    cross = held(lo32(u) * hi32(v) + cross);
+    cross = held(hi32(u) * lo32(v) + cross);
+    cross = held(lo32(s) * hi32(t) + cross);
+    cross = held(hi32(s) * lo32(t) + cross);
+    const uint64_t low = lo32(s) * lo32(t) + (lo32(u) * lo32(v) + (lo32(x) * lo32(y) + acc));
+    return add_to_high(held(low), cross);
+}
+
 // Beaver multiply x * D on Z_2^64 for one element; the triple is A[6i+1 .. 6i+5].
 __device__ __forceinline__ Pair beaver_mul(Pair x, Pair D, uint64_t zA)
 {
@@ -205,12 +258,13 @@ __device__ __forceinline__ Pair beaver_mul(Pair x, Pair D, uint64_t zA)
     const uint64_t b1 = mix64(zA + 4 * kGamma);
     const uint64_t c0 = mix64(zA + 5 * kGamma);
     const uint64_t a = a0 + a1, b = b0 + b1;                      // the dealer's triple (a, b, a * b)
-    const uint64_t c1 = a * b - c0;                               // dealer completes the sharing of c
     const uint64_t eps = (x.p0 + x.p1) - a;                       // opened: (x_0 - a_0) + (x_1 - a_1)
     const uint64_t del = (D.p0 - b0) + (D.p1 - b1);               // opened: each party's message, summed
     Pair out;
-    out.p0 = c0 + eps * (b0 + del) + del * a0;                    // = c0 + eps*b0 + del*a0 + eps*del
-    out.p1 = c1 + eps * b1 + del * a1;
+    // party 0: c_0 + eps * b_0 + del * a_0 + eps * del
+    out.p0 = sum_of_products(c0, eps, b0 + del, del, a0);
+    // party 1: c_1 + eps * b_1 + del * a_1, the dealer having completed c_1 = a * b - c_0
+    out.p1 = sum_of_products(0 - c0, a, b, eps, b1, del, a1);
     return out;
 }
 
