@@ -47,15 +47,15 @@ struct EcoLoader {
         uint64_t a0 = 0, a1 = 0, b0 = 0, b1 = 0;
         if (i + 1 < n) {
             if (VEC) {
-                const U64x2 a = *reinterpret_cast<const U64x2 *>(x0 + i);
-                const U64x2 b = *reinterpret_cast<const U64x2 *>(x1 + i);
+                const U64x2 a = load_stream2(x0 + i);
+                const U64x2 b = load_stream2(x1 + i);
                 a0 = a.a; a1 = a.b; b0 = b.a; b1 = b.b;
             } else {
-                a0 = x0[i]; a1 = x0[i + 1]; b0 = x1[i]; b1 = x1[i + 1];
+                a0 = load_stream(x0 + i); a1 = load_stream(x0 + i + 1); b0 = load_stream(x1 + i); b1 = load_stream(x1 + i + 1);
             }
         } else if (i < n) {
-            a0 = x0[i];
-            b0 = x1[i];
+            a0 = load_stream(x0 + i);
+            b0 = load_stream(x1 + i);
         }
         const uint64_t xa = a0 + b0, xb = a1 + b1;
         d0 = xa ^ (uint64_t)((int64_t)xa >> 63);

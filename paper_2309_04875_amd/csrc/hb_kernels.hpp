@@ -25,6 +25,21 @@ struct alignas(16) U64x2 {
     uint64_t a, b;
 };
 
+// Memory accesses with the non-temporal hint: every share is read once and every result written once, so
+// nothing is worth keeping in the caches (streaming 2-in / 2-out traffic runs about a tenth faster with it).
+typedef uint64_t u64x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ U64x2 load_stream2(const uint64_t *p)     // p is 16-byte aligned
+{
+    const u64x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u64x2_t *>(p));
+    return U64x2{v.x, v.y};
+}
+__device__ __forceinline__ void store_stream2(uint64_t *p, U64x2 v)  // p is 16-byte aligned
+{
+    __builtin_nontemporal_store(u64x2_t{v.a, v.b}, reinterpret_cast<u64x2_t *>(p));
+}
+__device__ __forceinline__ uint64_t load_stream(const uint64_t *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void store_stream(uint64_t *p, uint64_t v) { __builtin_nontemporal_store(v, p); }
+
 template <int W, int MODE, bool VEC>
 __global__ void __launch_bounds__(kBlock)
 group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups, int k, uint64_t seedB,
@@ -45,11 +60,9 @@ group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups
     uint64_t u0 = 0, u1 = 0;
 
     if (VEC && full && (L % 2 == 0)) {
-        const U64x2 *v0 = reinterpret_cast<const U64x2 *>(x0 + i0);
-        const U64x2 *v1 = reinterpret_cast<const U64x2 *>(x1 + i0);
 #pragma unroll
         for (int j = 0; j < L / 2; ++j) {
-            const U64x2 a = v0[j], b = v1[j];
+            const U64x2 a = load_stream2(x0 + i0 + 2 * j), b = load_stream2(x1 + i0 + 2 * j);
             u0 |= ((a.a >> k) & S::kField) << ((2 * j) * W % 64);
             u0 |= ((a.b >> k) & S::kField) << ((2 * j + 1) * W % 64);
             u1 |= ((b.a >> k) & S::kField) << ((2 * j) * W % 64);
@@ -66,8 +79,8 @@ group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups
         for (int j = 0; j < L; ++j) {
             uint64_t a = 0, b = 0;
             if (j < cnt) {
-                a = x0[i0 + j];
-                b = x1[i0 + j];
+                a = load_stream(x0 + i0 + j);
+                b = load_stream(x1 + i0 + j);
             }
             u0 |= ((a >> k) & S::kField) << (j * W % 64);
             u1 |= ((b >> k) & S::kField) << (j * W % 64);
@@ -85,8 +98,6 @@ group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups
 
     const uint64_t zA0 = seedA + (6 * i0 + 1) * kGamma;
     if (VEC && full && (L % 2 == 0)) {
-        U64x2 *w0 = reinterpret_cast<U64x2 *>(o0 + i0);
-        U64x2 *w1 = reinterpret_cast<U64x2 *>(o1 + i0);
 #pragma unroll
         for (int j = 0; j < L / 2; ++j) {
             Pair xe{0, 0}, xo{0, 0};
@@ -95,26 +106,26 @@ group_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, uint64_t groups
                     xe = Pair{xa[2 * j], xb[2 * j]};
                     xo = Pair{xa[2 * j + 1], xb[2 * j + 1]};
                 } else {
-                    const U64x2 a = reinterpret_cast<const U64x2 *>(x0 + i0)[j];
-                    const U64x2 b = reinterpret_cast<const U64x2 *>(x1 + i0)[j];
+                    const U64x2 a = load_stream2(x0 + i0 + 2 * j);
+                    const U64x2 b = load_stream2(x1 + i0 + 2 * j);
                     xe = Pair{a.a, b.a};
                     xo = Pair{a.b, b.b};
                 }
             }
             const Pair re = finish_element<W, MODE>(sum, wb, 2 * j, xe, zA0 + (uint64_t)(6 * (2 * j)) * kGamma);
             const Pair ro = finish_element<W, MODE>(sum, wb, 2 * j + 1, xo, zA0 + (uint64_t)(6 * (2 * j + 1)) * kGamma);
-            w0[j] = U64x2{re.p0, ro.p0};
-            w1[j] = U64x2{re.p1, ro.p1};
+            store_stream2(o0 + i0 + 2 * j, U64x2{re.p0, ro.p0});
+            store_stream2(o1 + i0 + 2 * j, U64x2{re.p1, ro.p1});
         }
     } else {
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             if (j < cnt) {
                 Pair x{0, 0};
-                if (op_of(MODE) == kRelu) x = kHold ? Pair{xa[j], xb[j]} : Pair{x0[i0 + j], x1[i0 + j]};
+                if (op_of(MODE) == kRelu) x = kHold ? Pair{xa[j], xb[j]} : Pair{load_stream(x0 + i0 + j), load_stream(x1 + i0 + j)};
                 const Pair r = finish_element<W, MODE>(sum, wb, j, x, zA0 + (uint64_t)(6 * j) * kGamma);
-                o0[i0 + j] = r.p0;
-                o1[i0 + j] = r.p1;
+                store_stream(o0 + i0 + j, r.p0);
+                store_stream(o1 + i0 + j, r.p1);
             }
         }
     }
@@ -129,14 +140,18 @@ open_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int binary, uint
     if (VEC) {
         const uint64_t i = 2 * t;
         if (i + 1 < n) {
-            const U64x2 a = reinterpret_cast<const U64x2 *>(x0)[t];
-            const U64x2 b = reinterpret_cast<const U64x2 *>(x1)[t];
-            reinterpret_cast<U64x2 *>(out)[t] = binary ? U64x2{a.a ^ b.a, a.b ^ b.b} : U64x2{a.a + b.a, a.b + b.b};
+            const U64x2 a = load_stream2(x0 + i);
+            const U64x2 b = load_stream2(x1 + i);
+            store_stream2(out + i, binary ? U64x2{a.a ^ b.a, a.b ^ b.b} : U64x2{a.a + b.a, a.b + b.b});
         } else if (i < n) {
-            out[i] = binary ? (x0[i] ^ x1[i]) : (x0[i] + x1[i]);
+            const uint64_t a = load_stream(x0 + i), b = load_stream(x1 + i);
+            store_stream(out + i, binary ? (a ^ b) : (a + b));
         }
     } else {
-        if (t < n) out[t] = binary ? (x0[t] ^ x1[t]) : (x0[t] + x1[t]);
+        if (t < n) {
+            const uint64_t a = load_stream(x0 + t), b = load_stream(x1 + t);
+            store_stream(out + t, binary ? (a ^ b) : (a + b));
+        }
     }
 }
 
@@ -196,11 +211,11 @@ struct ShareIO {
     {
         const uint64_t *t0 = x0 + tile0, *t1 = x1 + tile0;
         if (FULL || tile0 + e + 1 < n) {
-            a = *reinterpret_cast<const U64x2 *>(t0 + e);
-            b = *reinterpret_cast<const U64x2 *>(t1 + e);
+            a = load_stream2(t0 + e);
+            b = load_stream2(t1 + e);
         } else if (tile0 + e < n) {
-            a.a = t0[e];
-            b.a = t1[e];
+            a.a = load_stream(t0 + e);
+            b.a = load_stream(t1 + e);
         }
     }
     template <bool FULL>
@@ -208,11 +223,11 @@ struct ShareIO {
     {
         uint64_t *t0 = o0 + tile0, *t1 = o1 + tile0;
         if (FULL || tile0 + e + 1 < n) {
-            *reinterpret_cast<U64x2 *>(t0 + e) = U64x2{r0.p0, r1.p0};
-            *reinterpret_cast<U64x2 *>(t1 + e) = U64x2{r0.p1, r1.p1};
+            store_stream2(t0 + e, U64x2{r0.p0, r1.p0});
+            store_stream2(t1 + e, U64x2{r0.p1, r1.p1});
         } else if (tile0 + e < n) {
-            t0[e] = r0.p0;
-            t1[e] = r0.p1;
+            store_stream(t0 + e, r0.p0);
+            store_stream(t1 + e, r0.p1);
         }
     }
 };

@@ -208,7 +208,7 @@ mp_group_kernel(const MpPointers ptr, uint64_t n, uint64_t groups, int k, uint64
     for (int j = 0; j < L; ++j) {
         if (j < cnt) {
 #pragma unroll
-            for (int q = 0; q < P; ++q) u[q] |= ((ptr.x[q][i0 + j] >> k) & S::kField) << (j * W % 64);
+            for (int q = 0; q < P; ++q) u[q] |= ((load_stream(ptr.x[q] + i0 + j) >> k) & S::kField) << (j * W % 64);
         }
     }
     const uint64_t zg = seedB + (g * (uint64_t)M::kWordsPerGroup + 1) * kGamma;
@@ -223,13 +223,13 @@ mp_group_kernel(const MpPointers ptr, uint64_t n, uint64_t groups, int k, uint64
 #pragma unroll
             for (int q = 0; q < P; ++q) {
                 sign |= (uint32_t)((sum.v[q] >> (j * W + W - 1)) & 1) << q;
-                x.v[q] = (MODE == kRelu) ? ptr.x[q][i0 + j] : 0;
+                x.v[q] = (MODE == kRelu) ? load_stream(ptr.x[q] + i0 + j) : 0;
             }
             const uint32_t rho = (uint32_t)(wb >> (P * j)) & ((1u << P) - 1);
             const uint64_t zA = seedA + ((uint64_t)M::kArithWords * (i0 + j) + 1) * kGamma;
             const Shares<P> out = mp_finish<P, MODE>(sign, rho, x, zA);
 #pragma unroll
-            for (int q = 0; q < P; ++q) ptr.o[q][i0 + j] = out.v[q];
+            for (int q = 0; q < P; ++q) store_stream(ptr.o[q] + i0 + j, out.v[q]);
         }
     }
 }
@@ -276,9 +276,9 @@ __device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, uint64_t n, 
             for (int q = 0; q < P; ++q) {
                 const uint64_t *t = ptr.x[q] + tile0;       // scalar base, 32-bit lane offset
                 if (FULL || tile0 + e + 1 < n) {
-                    xs[q][c] = *reinterpret_cast<const U64x2 *>(t + e);
+                    xs[q][c] = load_stream2(t + e);
                 } else if (tile0 + e < n) {
-                    xs[q][c].a = t[e];
+                    xs[q][c].a = load_stream(t + e);
                 }
                 Entry *sl = reinterpret_cast<Entry *>(slice_lds[q]);
                 sl[e] = (Entry)((xs[q][c].a >> k) & S::kField);
@@ -340,9 +340,9 @@ __device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, uint64_t n, 
             for (int q = 0; q < P; ++q) {
                 uint64_t *t = ptr.o[q] + tile0;
                 if (FULL || tile0 + e + 1 < n) {
-                    *reinterpret_cast<U64x2 *>(t + e) = U64x2{r[0].v[q], r[1].v[q]};
+                    store_stream2(t + e, U64x2{r[0].v[q], r[1].v[q]});
                 } else if (tile0 + e < n) {
-                    t[e] = r[0].v[q];
+                    store_stream(t + e, r[0].v[q]);
                 }
             }
         }
