@@ -24,13 +24,13 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 BYTES_PER_ELEMENT = 32         # two int64 shares read, two written
 
 # HBM traffic of one launch of hb::tile_batch_kernel<8, relu> on this workload, from the rocprofv3 --pmc runs
-# summarised in profiles/tile_batch_kernel_w8_relu_resnet18_b512.txt: FETCH_SIZE 2228373.0 KiB scaled by 2.0
-# (what the counter under-reads for a plain streaming kernel of known size), WRITE_SIZE 4456448.0 KiB scaled by 1.0.
-PROFILED_TRAFFIC_BYTES = (2228373.0 * 2.0 + 4456448.0 * 1.0) * 1024.0
+# summarised in profiles/tile_batch_kernel_w8_relu_resnet18_b512.txt: FETCH_SIZE 2228395.7 KiB scaled by 2.0
+# (what the counter under-reads for a plain streaming kernel of known size), WRITE_SIZE 4456448.1 KiB scaled by 1.0.
+PROFILED_TRAFFIC_BYTES = (2228395.7 * 2.0 + 4456448.1 * 1.0) * 1024.0
 PROFILED_ELEMENTS = 285212672
 # Vector-ALU instructions per wavefront of the same kernel (SQ_INSTS_VALU / SQ_WAVES, profiles/
 # tile_kernel_w8_w64_valu_counters.txt); a wavefront covers 512 elements.
-VALU_INSTS_PER_WAVE = 2193.0
+VALU_INSTS_PER_WAVE = 2069.6
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9      # CUs x SIMDs x lanes per clock x 2.4 GHz = 39.3e12 32-bit lane-ops/s
 
 

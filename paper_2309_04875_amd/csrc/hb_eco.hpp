@@ -111,18 +111,35 @@ eco_scan_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int chunks, 
         }
     }
 
-    // per-position totals of the wavefront: bit b of plane j is set in popcount(ballot) lanes, each worth 2^j
-    unsigned int mine = 0;                                            // lane b ends up with the total for position b
-    for (int b = 0; b < 64; ++b) {
-        unsigned int total = 0;
+    // Per-position totals of the wavefront.  The 64 lanes' bit-sliced counters are summed by a butterfly of six
+    // bit-sliced additions (lane l with lane l ^ 32, ^ 16, ... ^ 1; a full adder per plane is two v_bitop3_b32 per
+    // half), after which every lane holds the wavefront's totals, still bit-sliced: up to 16 + 6 planes.  Lane b
+    // then reads position b out of every plane.
+    uint64_t tot[kEcoPlanes + 6];
 #pragma unroll
-        for (int j = 0; j < kEcoPlanes; ++j) {
-            if (j < live_planes) {
-                const unsigned long long votes = __ballot((plane[j] >> b) & 1);
-                total += (unsigned int)__popcll(votes) << j;
+    for (int j = 0; j < kEcoPlanes + 6; ++j) tot[j] = j < kEcoPlanes ? plane[j] : 0;
+#pragma unroll
+    for (int level = 0; level < 6; ++level) {
+        const int stride = 32 >> level;
+        uint64_t carry = 0;
+#pragma unroll
+        for (int j = 0; j < kEcoPlanes + 6; ++j) {
+            if (j < live_planes + level) {                            // planes above are still zero (uniform)
+                const uint32_t lo = __shfl_xor((uint32_t)tot[j], stride, kWave);
+                const uint32_t hi = __shfl_xor((uint32_t)(tot[j] >> 32), stride, kWave);
+                const uint64_t other = ((uint64_t)hi << 32) | lo;
+                const uint64_t sum = bit3(tot[j], other, carry, false);
+                carry = bit3(tot[j], other, carry, true);
+                tot[j] = sum;
+            } else if (j == live_planes + level) {
+                tot[j] = carry;                                       // the sum is one plane longer
             }
         }
-        if (lane == b) mine = total;
+    }
+    unsigned int mine = 0;                                            // lane b: the total for position b
+#pragma unroll
+    for (int j = 0; j < kEcoPlanes + 6; ++j) {
+        if (j < live_planes + 6) mine |= (unsigned int)((tot[j] >> lane) & 1) << j;
     }
     partial[wv][lane] = mine;
     __syncthreads();
