@@ -282,8 +282,8 @@ int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened
         // gather the later tensors of the same width that can share the launch
         hb::BatchArgs args = {};
         auto add = [&](const hb_tensor &t) {
-            const uint64_t L = 64 / (uint64_t)w;    // tile-kernel widths have L = floor(64 / w) <= 16
-            const uint64_t tiles = (t.n + hb::kWave * L - 1) / (hb::kWave * L);
+            const uint64_t per_tile = (uint64_t)hb::tile_elements(w);
+            const uint64_t tiles = (t.n + per_tile - 1) / per_tile;
             hb::BatchTensor &d = args.t[args.count];
             d.x0 = (const uint64_t *)t.share0;
             d.x1 = (const uint64_t *)t.share1;

@@ -2,9 +2,9 @@
 //
 //   group_kernel       one thread per group of L = min(64/W, 32) consecutive elements: packs the slices of its
 //                      elements into two SWAR words, runs the circuit (gate 0, all prefix rounds, sign), then
-//                      finishes its elements one by one (B2A, Beaver multiply).  No LDS.  Used for L = 1, L > 16
+//                      finishes its elements one by one (B2A, Beaver multiply).  No LDS.  Used for w > 32
 //                      and for buffers that are only 8-byte aligned.
-//   tile_kernel        one wavefront per 64 groups, coalesced 16-byte memory traffic per lane, slices and sign
+//   tile_kernel        one wavefront per 64 groups (32 for w <= 3), coalesced 16-byte memory traffic per lane, slices and sign
 //   tile_batch_kernel  words exchanged through wave-private LDS (described above the kernel).  The batch form
 //                      serves several tensors of one width; tile_sim_kernel is the float-in / float-out form.
 //   open_kernel        share0 + share1 or share0 ^ share1.
@@ -157,9 +157,9 @@ open_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int binary, uint
 
 
 // ------------------------------------------------------------------------------------------------
-// Tile kernel (slice widths with 2 <= L <= 16, 16-byte aligned buffers).
+// Tile kernel (slice widths up to 32, 16-byte aligned buffers).
 //
-// A wavefront owns a tile of 64*L consecutive elements = 64 groups.  Memory traffic and the
+// A wavefront owns a tile of 64*L consecutive elements = 64 groups (32 groups when L > 16).  Memory traffic and the
 // per-element arithmetic are laid out for coalescing: lane l loads / finishes / stores the element
 // pairs (2(c*64 + l), +1), so every load and store instruction of the wave covers 1 KiB of
 // consecutive addresses.  The circuit is laid out for dealer-word sharing: lane l evaluates group l
@@ -180,13 +180,26 @@ __device__ __forceinline__ void wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Geometry of a wave-tile for slice width w, shared by the kernels and the host code that counts tiles.
+// A wavefront takes 64 groups, or 32 when a group has more than 16 elements (w <= 3): a lane then still owns
+// at most 8 element pairs, which is what fits in registers, and only the lower half of the lanes runs the
+// (short) circuit.
+constexpr int tile_lanes_per_word(int w) { return 64 / w > 32 ? 32 : 64 / w; }
+constexpr int tile_groups(int w) { return tile_lanes_per_word(w) > 16 ? 32 : 64; }
+constexpr int tile_elements(int w) { return tile_groups(w) * tile_lanes_per_word(w); }
+
 template <int W>
 struct TileTraits {
     using S = Shape<W>;
     static constexpr int L = S::L;
-    static constexpr bool kSupported = (L >= 2 && L <= 16);
-    static constexpr int kTile = kWave * L;                     // elements per wavefront
-    static constexpr int kPairs = (L + 1) / 2;                  // element pairs per lane (last may be idle when L is odd)
+    static constexpr bool kSupported = (L >= 2);                // every width below 33
+    // the group lane publishes party 1's sign bit of a field next to party 0's; one-bit fields have no room for
+    // that, but their 32 fields leave the upper half of the word free
+    static constexpr int kSign1 = (W == 1) ? 32 : 1;
+    static constexpr bool kSimSupported = (W >= 4 && W <= 32);  // widths of the float-in / float-out kernel
+    static constexpr int kGroups = tile_groups(W);              // groups per wavefront
+    static constexpr int kTile = tile_elements(W);              // elements per wavefront
+    static constexpr int kPairs = (kTile / 2 + kWave - 1) / kWave;   // element pairs per lane (the last may be idle)
     // W in {4, 8, 16, 32}: a pair of fields is an addressable LDS item (1, 2, 4, 8 bytes), so owners can
     // write their pair straight into the group's packed word.  Other widths go through one entry per element.
     static constexpr bool kPacked = (W == 4 || W == 8 || W == 16 || W == 32);
@@ -304,7 +317,7 @@ __device__ __forceinline__ void tile_body_impl(const IO &io, uint64_t n, int k, 
     using T = TileTraits<W>;
     using S = Shape<W>;
     constexpr int L = T::L;
-    static_assert(T::kSupported, "tile kernel needs 2 <= L <= 16");
+    static_assert(T::kSupported, "tile kernel needs W <= 32");
     const uint64_t tile0 = tile * T::kTile;
 
     // ---- owners: load, slice, deposit -------------------------------------------------------
@@ -335,27 +348,27 @@ __device__ __forceinline__ void tile_body_impl(const IO &io, uint64_t n, int k, 
     wave_sync();
 
     // ---- group lanes: collect fields, run the circuit, publish the verdict ----------------------
-    uint64_t u0 = 0, u1 = 0;
-    if constexpr (T::kPacked) {
-        u0 = reinterpret_cast<const uint64_t *>(slice_lds)[lane];
-        u1 = reinterpret_cast<const uint64_t *>(slice_lds + kWave * 8)[lane];
-    } else {
-        using Entry = typename T::Entry;
-        const Entry *slices = reinterpret_cast<const Entry *>(slice_lds);
+    if (T::kGroups == kWave || lane < T::kGroups) {
+        uint64_t u0 = 0, u1 = 0;
+        if constexpr (T::kPacked) {
+            u0 = reinterpret_cast<const uint64_t *>(slice_lds)[lane];
+            u1 = reinterpret_cast<const uint64_t *>(slice_lds + kWave * 8)[lane];
+        } else {
+            using Entry = typename T::Entry;
+            const Entry *slices = reinterpret_cast<const Entry *>(slice_lds);
 #pragma unroll
-        for (int j = 0; j < L; ++j) {
-            const Entry en = slices[lane * L + j];
-            u0 |= (uint64_t)(en & (Entry)S::kField) << (j * W);
-            u1 |= (uint64_t)(en >> T::kHalf) << (j * W);
+            for (int j = 0; j < L; ++j) {
+                const Entry en = slices[lane * L + j];
+                u0 |= (uint64_t)(en & (Entry)S::kField) << (j * W);
+                u1 |= (uint64_t)(en >> T::kHalf) << (j * W);
+            }
         }
-    }
-    const uint64_t g = tile * kWave + lane;
-    const uint64_t zg = seedB + (g * (uint64_t)S::words_per_group(shared_of(MODE)) + 1) * kGamma;
-    const Pair sum = a2b_sum<W, shared_of(MODE)>(u0, u1, zg);
-    {
-        // sign of field j: party 0 at bit jW, party 1 at bit jW + 1
+        const uint64_t g = tile * T::kGroups + lane;
+        const uint64_t zg = seedB + (g * (uint64_t)S::words_per_group(shared_of(MODE)) + 1) * kGamma;
+        const Pair sum = a2b_sum<W, shared_of(MODE)>(u0, u1, zg);
+        // sign of field j: party 0 at bit jW, party 1 at bit jW + kSign1
         const uint64_t ones = S::ones();
-        const uint64_t sg = ((sum.p0 >> (W - 1)) & ones) | (((sum.p1 >> (W - 1)) & ones) << 1);
+        const uint64_t sg = ((sum.p0 >> (W - 1)) & ones) | (((sum.p1 >> (W - 1)) & ones) << T::kSign1);
         uint64_t wb = 0;
         if (op_of(MODE) != kSign) wb = mix64(zg + (uint64_t)S::b2a_word(shared_of(MODE)) * kGamma);
         verdict[lane] = U64x2{sg, wb};
@@ -379,9 +392,9 @@ __device__ __forceinline__ void tile_body_impl(const IO &io, uint64_t n, int k, 
             for (int h = 0; h < 2; ++h) {
                 const U64x2 v = h ? v1 : v0;
                 const int j = h ? (split ? 0 : j0 + 1) : j0;
-                // only bits 0 and 1 of each shifted word are used
-                const uint32_t sg = (uint32_t)(v.a >> (j * W));
-                const Pair sign{sg & 1u, (sg >> 1) & 1u};
+                // only two bits of each shifted word are used
+                const uint64_t sg = v.a >> (j * W);
+                const Pair sign{sg & 1u, (sg >> T::kSign1) & 1u};
                 if (op_of(MODE) == kSign) {
                     r[h] = sign;
                 } else {
