@@ -96,8 +96,8 @@ typedef struct hb_tensor {
 
 /*
  * A set of ReLU layers' tensors in as few launches as possible (the per-layer (k, m) of Sec. 4.2 are
- * fixed offline, so a whole set can be issued at once; one launch per distinct slice width when the
- * buffers are 16-byte aligned).  `tensors` is a HOST array of `count` descriptors, read before the
+ * fixed offline, so a whole set can be issued at once; one launch per distinct slice width up to 32,
+ * up to 24 tensors per launch; wider slices take one launch per tensor).  `tensors` is a HOST array of `count` descriptors, read before the
  * call returns.  The result for every tensor is bit-for-bit what hb_relu (hb_drelu) gives for that
  * tensor alone.  All descriptors are validated before anything is enqueued; besides the per-tensor
  * rules, no output of one tensor may overlap any buffer of another.  opened_bits receives the sum

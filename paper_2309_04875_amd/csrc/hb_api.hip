@@ -272,8 +272,7 @@ int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened
         bits += mode_bits(mode, first.k, first.m, first.n);
         if (first.n == 0) continue;
         const hb::BatchLauncher bl = hb::launcher_table().batch[mode][w - 1];
-        const void *p0[4] = {first.share0, first.share1, first.out0, first.out1};
-        if (bl == nullptr || hb::force_group_kernel() || !all_aligned16(p0, 4)) {
+        if (bl == nullptr || hb::force_group_kernel()) {
             const int st = run(mode, first.share0, first.share1, first.n, first.k, first.m, first.seed, first.out0,
                                first.out1, nullptr, stream);
             if (st != HB_OK) return st;
@@ -306,8 +305,6 @@ int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened
         for (size_t j = i + 1; j < count; ++j) {
             const hb_tensor &t = tensors[j];
             if (taken[j] || t.m - t.k != w || t.n == 0) continue;
-            const void *pj[4] = {t.share0, t.share1, t.out0, t.out1};
-            if (!all_aligned16(pj, 4)) continue;
             if (args.count == hb::kBatchMax) {
                 const int st = flush();
                 if (st != HB_OK) return st;

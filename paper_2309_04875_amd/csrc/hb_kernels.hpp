@@ -2,8 +2,7 @@
 //
 //   group_kernel       one thread per group of L = min(64/W, 32) consecutive elements: packs the slices of its
 //                      elements into two SWAR words, runs the circuit (gate 0, all prefix rounds, sign), then
-//                      finishes its elements one by one (B2A, Beaver multiply).  No LDS.  Used for w > 32
-//                      and for buffers that are only 8-byte aligned.
+//                      finishes its elements one by one (B2A, Beaver multiply).  No LDS.  Used for w > 32.
 //   tile_kernel        one wavefront per 64 groups (32 for w <= 3), coalesced 16-byte memory traffic per lane, slices and sign
 //   tile_batch_kernel  words exchanged through wave-private LDS (described above the kernel).  The batch form
 //                      serves several tensors of one width; tile_sim_kernel is the float-in / float-out form.
@@ -157,7 +156,7 @@ open_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int binary, uint
 
 
 // ------------------------------------------------------------------------------------------------
-// Tile kernel (slice widths up to 32, 16-byte aligned buffers).
+// Tile kernel (slice widths up to 32).
 //
 // A wavefront owns a tile of 64*L consecutive elements = 64 groups (32 groups when L > 16).  Memory traffic and the
 // per-element arithmetic are laid out for coalescing: lane l loads / finishes / stores the element
@@ -219,13 +218,24 @@ struct TileTraits {
 struct ShareIO {
     const uint64_t *x0, *x1;
     uint64_t *o0, *o1;
+    bool vec16;      // all four arrays are 16-byte aligned (uniform): pairs travel as one 16-byte access, else as two
+    __device__ __forceinline__ ShareIO(const uint64_t *a, const uint64_t *b, uint64_t *c, uint64_t *d)
+        : x0(a), x1(b), o0(c), o1(d),
+          vec16((((uintptr_t)a | (uintptr_t)b | (uintptr_t)c | (uintptr_t)d) & 15u) == 0)
+    {
+    }
     template <bool FULL>
     __device__ __forceinline__ void load_pair(uint64_t tile0, unsigned e, uint64_t n, U64x2 &a, U64x2 &b) const
     {
         const uint64_t *t0 = x0 + tile0, *t1 = x1 + tile0;
         if (FULL || tile0 + e + 1 < n) {
-            a = load_stream2(t0 + e);
-            b = load_stream2(t1 + e);
+            if (vec16) {
+                a = load_stream2(t0 + e);
+                b = load_stream2(t1 + e);
+            } else {
+                a = U64x2{load_stream(t0 + e), load_stream(t0 + e + 1)};
+                b = U64x2{load_stream(t1 + e), load_stream(t1 + e + 1)};
+            }
         } else if (tile0 + e < n) {
             a.a = load_stream(t0 + e);
             b.a = load_stream(t1 + e);
@@ -236,8 +246,15 @@ struct ShareIO {
     {
         uint64_t *t0 = o0 + tile0, *t1 = o1 + tile0;
         if (FULL || tile0 + e + 1 < n) {
-            store_stream2(t0 + e, U64x2{r0.p0, r1.p0});
-            store_stream2(t1 + e, U64x2{r0.p1, r1.p1});
+            if (vec16) {
+                store_stream2(t0 + e, U64x2{r0.p0, r1.p0});
+                store_stream2(t1 + e, U64x2{r0.p1, r1.p1});
+            } else {
+                store_stream(t0 + e, r0.p0);
+                store_stream(t0 + e + 1, r1.p0);
+                store_stream(t1 + e, r0.p1);
+                store_stream(t1 + e + 1, r1.p1);
+            }
         } else if (tile0 + e < n) {
             store_stream(t0 + e, r0.p0);
             store_stream(t1 + e, r0.p1);
@@ -439,7 +456,7 @@ tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t 
     const int lane = threadIdx.x % kWave, wv = wave_index();
     const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     if (tile * T::kTile >= n) return;        // whole wavefront beyond the tensor (uniform per wave)
-    tile_body<W, MODE>(ShareIO{x0, x1, o0, o1}, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+    tile_body<W, MODE>(ShareIO(x0, x1, o0, o1), n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 // Several tensors of one slice width in a single launch.  The descriptors travel in the kernel
@@ -474,7 +491,7 @@ tile_batch_kernel(const BatchArgs args)
     while (gt >= args.tile_end[ti]) ++ti;                                     // uniform per wave, at most kBatchMax steps
     const uint64_t tile = gt - (ti ? args.tile_end[ti - 1] : 0);
     const BatchTensor &d = args.t[ti];
-    tile_body<W, MODE>(ShareIO{d.x0, d.x1, d.o0, d.o1}, d.n, d.k, d.seedB, d.seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+    tile_body<W, MODE>(ShareIO(d.x0, d.x1, d.o0, d.o1), d.n, d.k, d.seedB, d.seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 // The simulator kernel: ReLU on plaintext floats through the whole protocol, 8 bytes of traffic per element.

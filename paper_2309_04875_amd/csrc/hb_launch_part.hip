@@ -18,7 +18,7 @@ hipError_t launch_group(const uint64_t *x0, const uint64_t *x1, uint64_t n, int 
     const uint64_t blocks = (groups + hb::kBlock - 1) / hb::kBlock;
     if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
     if constexpr (hb::TileTraits<W>::kSupported) {
-        if (vec16 && !hb::force_group_kernel()) {
+        if (!hb::force_group_kernel()) {
             const uint64_t wave_tiles = (n + hb::TileTraits<W>::kTile - 1) / hb::TileTraits<W>::kTile;
             const uint64_t tiles = (wave_tiles + hb::kWavesPerBlock - 1) / hb::kWavesPerBlock;
             if (tiles > 0x7fffffffull) return hipErrorInvalidConfiguration;
