@@ -225,7 +225,7 @@ def main():
                      "kernel": "hb::tile_batch_kernel<8, relu>",
                      "avg_launch_ms": avg_launch_ms, "kernel_ms_per_step": kernel_ms_per_step,
                      "algorithmic_bytes_per_element": BYTES_PER_ELEMENT},
-        # the kernel is bound by vector-ALU issue (VALUBusy 96 %), so the HBM fraction above cannot reach 1;
+        # the kernel is bound by vector-ALU issue (VALUBusy 99 %), so the HBM fraction above cannot reach 1;
         # this is the same launch priced against the chip's 32-bit integer lane-op rate
         "roofline_alu": {"bound": "alu", "achieved": valu_lane_ops / (avg_launch_ms * 1e-3) / 1e12,
                          "peak": VALU_PEAK_LANE_OPS / 1e12, "unit": "T lane-ops/s",
