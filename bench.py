@@ -173,6 +173,29 @@ def main():
         ms = _time_launches(lambda: hb.hb_sim_relu_f32(xf, k, m, seed0, 1, yf), 100, torch)
         extra["sim_relu_f32_w8_elems_per_s"] = spec0.n / (ms * 1e-3)       # 8 B per element; bound by VALU like hb_relu
         del xf, yf
+        # the one-image set (17 tensors, 557,056 elements, per-tensor (k, m)) is launch-bound: per-tensor calls, the
+        # batched call (one launch per distinct width) and the batched call replayed from a HIP graph
+        small = []
+        for spec in workloads.resnet18_cifar():
+            _, a, b = workloads.materialize_on_device(spec, dev)
+            small.append((a, b, torch.empty_like(a), torch.empty_like(b), spec.k, spec.m,
+                          hb.hb_tensor_seed(ROOT_SEED, spec.tensor_id)))
+        n_small = sum(t[0].numel() for t in small)
+        small_batch = hb.make_batch(small)
+        ms = _time_launches(lambda: [hb.hb_relu(a, b, kk, mm, sd, c, d) for (a, b, c, d, kk, mm, sd) in small], 200, torch)
+        extra["one_image_set_us_per_tensor_calls"] = ms * 1e3
+        ms = _time_launches(lambda: hb.hb_relu_batch(small_batch), 200, torch)
+        extra["one_image_set_us_batched_call"] = ms * 1e3
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                hb.hb_relu_batch(small_batch)
+        torch.cuda.synchronize()
+        ms = _time_launches(graph.replay, 200, torch)
+        extra["one_image_set_us_graph_replay"] = ms * 1e3
+        extra["one_image_set_elements"] = n_small
+        del graph, small, small_batch
         counts = torch.empty(64, dtype=torch.int64, device=dev)
         ms = _time_launches(lambda: hb.hb_eco_scan(s0, s1, counts), 300, torch)
         extra["eco_scan_elems_per_s"] = spec0.n / (ms * 1e-3)
