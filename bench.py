@@ -127,6 +127,24 @@ def main():
     achieved_gbs = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
     valu_lane_ops = VALU_INSTS_PER_WAVE * 64.0 * (n_total / 512.0)     # instructions x lanes x wavefronts
 
+    # ---- the shader clock the GPU sustains under this kernel: a one-wavefront probe on a second stream while
+    # steps of the workload run (the board is power-limited under this load; nominal clock 2.4 GHz) -----------
+    def clock_under(load_fn, launches):
+        side = torch.cuda.Stream()
+        stamps = torch.zeros(2, dtype=torch.int64, device=dev)
+        torch.cuda.synchronize()
+        for _ in range(launches):
+            load_fn()
+        with torch.cuda.stream(side):
+            hb.hb_clock_probe(3000, stamps)
+        for _ in range(launches):
+            load_fn()
+        torch.cuda.synchronize()
+        ticks = stamps.cpu().tolist()
+        return 100.0 * ticks[0] / max(ticks[1], 1)
+
+    core_clock_mhz = clock_under(step, 3) if not args.no_extra else None
+
     # ---- side figures, outside the timed region ---------------------------------------------
     spec0, s0, s1, o0, o1, seed0 = tensors[0]
     extra = {"opened_bits_per_element": opened / n_total,
@@ -157,6 +175,7 @@ def main():
         extra["relu_w64_elems_per_s"] = spec0.n / (ms * 1e-3)
         extra["relu_w64_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         ms = _time_launches(lambda: hb.hb_drelu(s0, s1, k, m, seed0, o0, o1), 300, torch)
+        extra["drelu_w8_shader_clock_mhz"] = clock_under(lambda: hb.hb_drelu(s0, s1, k, m, seed0, o0, o1), 40)
         extra["drelu_w8_elems_per_s"] = spec0.n / (ms * 1e-3)
         extra["drelu_w8_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         ms = _time_launches(lambda: hb.hb_open(s0, s1, False, out=o0), 300, torch)
@@ -253,7 +272,8 @@ def main():
         "roofline_alu": {"bound": "alu", "achieved": valu_lane_ops / (avg_launch_ms * 1e-3) / 1e12,
                          "peak": VALU_PEAK_LANE_OPS / 1e12, "unit": "T lane-ops/s",
                          "frac": valu_lane_ops / (avg_launch_ms * 1e-3) / VALU_PEAK_LANE_OPS,
-                         "valu_instructions_per_element": VALU_INSTS_PER_WAVE / 8.0},
+                         "valu_instructions_per_element": VALU_INSTS_PER_WAVE / 8.0,
+                         "shader_clock_mhz_under_this_kernel": core_clock_mhz},
         "cpu_baseline": cpu,
         "extra": extra,
     }
