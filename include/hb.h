@@ -230,7 +230,7 @@ HB_API uint64_t hb_opened_bits_ex(int relu, int k, int m, size_t n, int dealer);
 /*
  * Measurement aid, not part of the protocol: the shader clock the GPU sustains while other work runs.  One
  * wavefront reads the shader-clock counter and the constant 100 MHz counter, executes `spins` iterations of a
- * short dependent arithmetic loop (bounded: it ends after exactly `spins` iterations, at most 2^26), and reads
+ * short dependent arithmetic loop (bounded: it ends after exactly `spins` iterations, at most 2^20), and reads
  * both counters again.  stamps: DEVICE pointer to 2 uint64 (8-byte aligned): {shader-clock ticks, 100 MHz
  * ticks} of the loop; clock in MHz = 100 * stamps[0] / stamps[1].  Enqueue it on a stream of its own next to
  * the kernels of interest (bench.py does) to see the clock under that load.

@@ -628,7 +628,7 @@ int hb_eco_scan(const int64_t *share0, const int64_t *share1, size_t n, uint64_t
 
 int hb_clock_probe(uint64_t spins, uint64_t *stamps, void *stream)
 {
-    if (stamps == nullptr || spins == 0 || spins > (1ull << 26)) return HB_EINVAL;
+    if (stamps == nullptr || spins == 0 || spins > (1ull << 20)) return HB_EINVAL;
     if (((uintptr_t)stamps & 7u) != 0) return HB_EALIGN;
     const int st = check_device_buffer(stamps, 2);
     if (st != HB_OK) return st;
