@@ -15,12 +15,12 @@ hipError_t launch_mp(const hb::MpPointers &ptr, uint64_t n, int k, uint64_t seed
                      hipStream_t stream)
 {
     if constexpr (hb::MpTileTraits<W, P>::kSupported) {
-        if (vec16 && !hb::force_group_kernel()) {
+        if (!hb::force_group_kernel()) {
             const uint64_t wave_tiles = (n + hb::MpTileTraits<W, P>::kTile - 1) / hb::MpTileTraits<W, P>::kTile;
             const uint64_t blocks = (wave_tiles + hb::kWavesPerBlock - 1) / hb::kWavesPerBlock;
             if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
             hipLaunchKernelGGL((hb::mp_tile_kernel<W, P, MODE>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, stream, ptr,
-                               n, k, seedB, seedA);
+                               vec16, n, k, seedB, seedA);
             return hipGetLastError();
         }
     }
