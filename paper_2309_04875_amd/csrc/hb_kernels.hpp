@@ -26,13 +26,15 @@ struct alignas(16) U64x2 {
 
 // Memory accesses with the non-temporal hint: every share is read once and every result written once, so
 // nothing is worth keeping in the caches (streaming 2-in / 2-out traffic runs about a tenth faster with it).
-typedef uint64_t u64x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ U64x2 load_stream2(const uint64_t *p)     // p is 16-byte aligned
+// A pair of elements travels as one 16-byte access; the type only promises the 8-byte alignment the interface
+// requires (the hardware takes 16-byte global accesses at any 4-byte alignment).
+typedef uint64_t u64x2_t __attribute__((ext_vector_type(2), aligned(8)));
+__device__ __forceinline__ U64x2 load_stream2(const uint64_t *p)
 {
     const u64x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u64x2_t *>(p));
     return U64x2{v.x, v.y};
 }
-__device__ __forceinline__ void store_stream2(uint64_t *p, U64x2 v)  // p is 16-byte aligned
+__device__ __forceinline__ void store_stream2(uint64_t *p, U64x2 v)
 {
     __builtin_nontemporal_store(u64x2_t{v.a, v.b}, reinterpret_cast<u64x2_t *>(p));
 }
@@ -218,24 +220,13 @@ struct TileTraits {
 struct ShareIO {
     const uint64_t *x0, *x1;
     uint64_t *o0, *o1;
-    bool vec16;      // all four arrays are 16-byte aligned (uniform): pairs travel as one 16-byte access, else as two
-    __device__ __forceinline__ ShareIO(const uint64_t *a, const uint64_t *b, uint64_t *c, uint64_t *d)
-        : x0(a), x1(b), o0(c), o1(d),
-          vec16((((uintptr_t)a | (uintptr_t)b | (uintptr_t)c | (uintptr_t)d) & 15u) == 0)
-    {
-    }
     template <bool FULL>
     __device__ __forceinline__ void load_pair(uint64_t tile0, unsigned e, uint64_t n, U64x2 &a, U64x2 &b) const
     {
         const uint64_t *t0 = x0 + tile0, *t1 = x1 + tile0;
         if (FULL || tile0 + e + 1 < n) {
-            if (vec16) {
-                a = load_stream2(t0 + e);
-                b = load_stream2(t1 + e);
-            } else {
-                a = U64x2{load_stream(t0 + e), load_stream(t0 + e + 1)};
-                b = U64x2{load_stream(t1 + e), load_stream(t1 + e + 1)};
-            }
+            a = load_stream2(t0 + e);
+            b = load_stream2(t1 + e);
         } else if (tile0 + e < n) {
             a.a = load_stream(t0 + e);
             b.a = load_stream(t1 + e);
@@ -246,15 +237,8 @@ struct ShareIO {
     {
         uint64_t *t0 = o0 + tile0, *t1 = o1 + tile0;
         if (FULL || tile0 + e + 1 < n) {
-            if (vec16) {
-                store_stream2(t0 + e, U64x2{r0.p0, r1.p0});
-                store_stream2(t1 + e, U64x2{r0.p1, r1.p1});
-            } else {
-                store_stream(t0 + e, r0.p0);
-                store_stream(t0 + e + 1, r1.p0);
-                store_stream(t1 + e, r0.p1);
-                store_stream(t1 + e + 1, r1.p1);
-            }
+            store_stream2(t0 + e, U64x2{r0.p0, r1.p0});
+            store_stream2(t1 + e, U64x2{r0.p1, r1.p1});
         } else if (tile0 + e < n) {
             store_stream(t0 + e, r0.p0);
             store_stream(t1 + e, r0.p1);
@@ -456,7 +440,7 @@ tile_kernel(const uint64_t *x0, const uint64_t *x1, uint64_t n, int k, uint64_t 
     const int lane = threadIdx.x % kWave, wv = wave_index();
     const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     if (tile * T::kTile >= n) return;        // whole wavefront beyond the tensor (uniform per wave)
-    tile_body<W, MODE>(ShareIO(x0, x1, o0, o1), n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+    tile_body<W, MODE>(ShareIO{x0, x1, o0, o1}, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 // Several tensors of one slice width in a single launch.  The descriptors travel in the kernel
@@ -491,7 +475,7 @@ tile_batch_kernel(const BatchArgs args)
     while (gt >= args.tile_end[ti]) ++ti;                                     // uniform per wave, at most kBatchMax steps
     const uint64_t tile = gt - (ti ? args.tile_end[ti - 1] : 0);
     const BatchTensor &d = args.t[ti];
-    tile_body<W, MODE>(ShareIO(d.x0, d.x1, d.o0, d.o1), d.n, d.k, d.seedB, d.seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+    tile_body<W, MODE>(ShareIO{d.x0, d.x1, d.o0, d.o1}, d.n, d.k, d.seedB, d.seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 // The simulator kernel: ReLU on plaintext floats through the whole protocol, 8 bytes of traffic per element.

@@ -20,7 +20,7 @@ hipError_t launch_mp(const hb::MpPointers &ptr, uint64_t n, int k, uint64_t seed
             const uint64_t blocks = (wave_tiles + hb::kWavesPerBlock - 1) / hb::kWavesPerBlock;
             if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
             hipLaunchKernelGGL((hb::mp_tile_kernel<W, P, MODE>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, stream, ptr,
-                               vec16, n, k, seedB, seedA);
+                               n, k, seedB, seedA);
             return hipGetLastError();
         }
     }

@@ -10,8 +10,8 @@
 //   - party 0 adds every public term.
 //
 //   mp_group_kernel   one thread per group, scalar 8-byte accesses: the remaining widths.
-//   mp_tile_kernel    one wavefront per 64 groups with coalesced accesses, as tile_kernel: slice widths 4..32
-//                     (vec16: every buffer is 16-byte aligned and a pair travels as one 16-byte access).
+//   mp_tile_kernel    one wavefront per 64 groups with coalesced 16-byte accesses, as tile_kernel: slice
+//                     widths 4..32.
 //
 // Algorithmic traffic: 16 P bytes per element.
 #pragma once
@@ -253,8 +253,8 @@ struct MpTileTraits {
 // Work of one wavefront on wave-tile `tile` (uniform over the wavefront).  FULL: the whole tile lies inside the
 // tensor, so no access needs a bounds check (every tile but the last).
 template <int W, int P, int MODE, bool FULL>
-__device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, bool vec16, uint64_t n, int k, uint64_t seedB,
-                                             uint64_t seedA, uint64_t tile, int lane, unsigned char (*slice_lds)[MpTileTraits<W, P>::kSliceBytes],
+__device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
+                                             uint64_t tile, int lane, unsigned char (*slice_lds)[MpTileTraits<W, P>::kSliceBytes],
                                              U64x2 *verdict)
 {
     using S = Shape<W>;
@@ -276,7 +276,7 @@ __device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, bool vec16, 
             for (int q = 0; q < P; ++q) {
                 const uint64_t *t = ptr.x[q] + tile0;       // scalar base, 32-bit lane offset
                 if (FULL || tile0 + e + 1 < n) {
-                    xs[q][c] = vec16 ? load_stream2(t + e) : U64x2{load_stream(t + e), load_stream(t + e + 1)};
+                    xs[q][c] = load_stream2(t + e);
                 } else if (tile0 + e < n) {
                     xs[q][c].a = load_stream(t + e);
                 }
@@ -340,12 +340,7 @@ __device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, bool vec16, 
             for (int q = 0; q < P; ++q) {
                 uint64_t *t = ptr.o[q] + tile0;
                 if (FULL || tile0 + e + 1 < n) {
-                    if (vec16) {
-                        store_stream2(t + e, U64x2{r[0].v[q], r[1].v[q]});
-                    } else {
-                        store_stream(t + e, r[0].v[q]);
-                        store_stream(t + e + 1, r[1].v[q]);
-                    }
+                    store_stream2(t + e, U64x2{r[0].v[q], r[1].v[q]});
                 } else if (tile0 + e < n) {
                     store_stream(t + e, r[0].v[q]);
                 }
@@ -356,7 +351,7 @@ __device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, bool vec16, 
 
 template <int W, int P, int MODE>
 __global__ void __launch_bounds__(kBlock)
-mp_tile_kernel(const MpPointers ptr, bool vec16, uint64_t n, int k, uint64_t seedB, uint64_t seedA)
+mp_tile_kernel(const MpPointers ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA)
 {
     using T = MpTileTraits<W, P>;
     static_assert(T::kSupported, "tile kernel needs 4 <= W <= 32");
@@ -366,9 +361,9 @@ mp_tile_kernel(const MpPointers ptr, bool vec16, uint64_t n, int k, uint64_t see
     const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     if (tile * T::kTile >= n) return;        // whole wavefront beyond the tensor
     if ((tile + 1) * T::kTile <= n)
-        mp_tile_body<W, P, MODE, true>(ptr, vec16, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+        mp_tile_body<W, P, MODE, true>(ptr, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
     else
-        mp_tile_body<W, P, MODE, false>(ptr, vec16, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+        mp_tile_body<W, P, MODE, false>(ptr, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 }  // namespace hb

@@ -13,7 +13,7 @@ __device__ __forceinline__ void probe_body(const uint64_t *x0, const uint64_t *x
     __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];
     const int lane = threadIdx.x % kWave, wv = wave_index();
     const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
-    tile_body_impl<W, MODE, true>(ShareIO(x0, x1, o0, o1), n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+    tile_body_impl<W, MODE, true>(ShareIO{x0, x1, o0, o1}, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
 #define PROBE(NAME, W, MODE)                                                                                        \
