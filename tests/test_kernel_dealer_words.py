@@ -31,6 +31,15 @@ def _expected(w, op, shared):
     return group + 1 + per_element * L
 
 
+def _expected_mp(w, op, parties):
+    R = 0 if w == 1 else (w - 1).bit_length()
+    L = min(64 // w, 64 // parties)
+    gates = 2 * R if R else 1                               # per adder: gate 0 and two per round but the last P-update
+    group = (parties - 1) * gates * (3 * parties - 1) + 1   # p - 1 adders, 3p - 1 words per gate, + the B2A word
+    per_element = {"relu": 4 * parties - 2, "drelu": parties - 1}[op]
+    return group + per_element * L
+
+
 @pytest.fixture(scope="module")
 def probe_asm():
     if not os.path.exists(HIPCC):
@@ -66,3 +75,12 @@ def _mix64_count(asm, kernel):
 ])
 def test_every_dealer_word_is_drawn(probe_asm, kernel, w, op, shared):
     assert _mix64_count(probe_asm, kernel) == _expected(w, op, shared)
+
+
+@pytest.mark.parametrize("kernel,w,op,parties", [
+    ("probe_p3_w8_relu", 8, "relu", 3),
+    ("probe_p3_w8_drelu", 8, "drelu", 3),
+    ("probe_p4_w8_relu", 8, "relu", 4),
+])
+def test_every_dealer_word_is_drawn_multi_party(probe_asm, kernel, w, op, parties):
+    assert _mix64_count(probe_asm, kernel) == _expected_mp(w, op, parties)
