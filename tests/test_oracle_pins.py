@@ -151,6 +151,33 @@ def test_opened_bits_table_and_scaling():
     assert oracle.opened_bits(True, 3, 3, 5) == 0 and oracle.opened_bits(True, 0, 65, 5) == 0
 
 
+def test_reduction_bands_of_the_paper(paper_examples):
+    """Sanity band, not an equality: the paper's reductions are end-to-end (linear layers and the parts of ReLU
+    that do not shrink included), ours are for the ReLU openings alone, so ours must reach at least the paper's
+    lower ends and sit at the paper's upper end for the widths its search keeps.  Kept bits: 64 x (9..13) % = 6..8.
+    Rounds of one ReLU: gate 0, ceil(log2 w) prefix rounds, B2A, multiply (the party-wise transcript has one message
+    per round); 9 on the full ring."""
+    p = paper_examples
+    base_bits = 29 * 64
+    kept = [w for w in range(1, 65)
+            if p["bits_discarded_pct_lo"] <= round(100.0 * (64 - w) / 64.0) <= p["bits_discarded_pct_hi"]]
+    assert kept == [6, 7, 8]
+    ratios = [base_bits / oracle.opened_bits(True, 12, 12 + w, 1) for w in kept]
+    # the multiply (128 bits) does not shrink: the ratio saturates just below the paper's best figure
+    assert all(p["bytes_reduction_lo"] < r for r in ratios)
+    assert abs(max(ratios) - p["bytes_reduction_hi"]) < 0.1 and max(ratios) <= p["bytes_reduction_hi"]
+    # zero-error strategy: 18..22 kept bits, no low cut
+    eco = [base_bits / oracle.opened_bits(True, 0, m, 1) for m in range(int(p["eco_kept_bits_lo"]), int(p["eco_kept_bits_hi"]) + 1)]
+    assert all(p["bytes_reduction_lo"] < r < p["bytes_reduction_hi"] for r in eco)
+
+    def rounds(w):
+        return 1 + (0 if w == 1 else (w - 1).bit_length()) + 2
+    assert rounds(64) == 9
+    # the paper's least reduction of rounds, 1.12x, is 9 / 8: widths 17..32; 9 / 6 = 1.5 at the kept widths
+    assert round(rounds(64) / rounds(32), 2) in (p["rounds_reduction_lo"], round(p["rounds_reduction_lo"] + 0.01, 2))
+    assert all(p["rounds_reduction_lo"] <= rounds(64) / rounds(w) <= p["rounds_reduction_hi"] for w in kept + [20, 22, 32])
+
+
 def test_opened_bits_shared_mask_variant():
     """One mask for P per prefix round: that round opens P ^ a once and two second operands, 3w bits."""
     for w in range(1, 65):
