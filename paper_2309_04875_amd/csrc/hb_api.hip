@@ -205,7 +205,7 @@ int run_mp(int op, const int64_t *const *shares, int parties, size_t n, int k, i
         const hb::MpLauncher f = hb::launcher_table().mp[parties - 3][op][m - k - 1];
         if (f == nullptr) return fail_hip(hipErrorInvalidDeviceFunction, "no kernel was built for this slice width");
         const hipError_t e = f(ptr, (uint64_t)n, k, hb::stream_word(seed, 0), hb::stream_word(seed, 1),
-                               all_aligned16(ptrs, 2 * parties), (hipStream_t)stream);
+                               (hipStream_t)stream);
         if (e != hipSuccess) return fail_hip(e, "kernel launch");
     }
     if (opened_bits) *opened_bits = hb_opened_bits_mp(op == hb::kRelu, parties, k, m, n);

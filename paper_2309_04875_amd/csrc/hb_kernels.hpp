@@ -382,7 +382,6 @@ __device__ __forceinline__ void tile_body_impl(const IO &io, uint64_t n, int k, 
     for (int c = 0; c < T::kPairs; ++c) {
         const int e = 2 * (c * kWave + lane);
         if (e < T::kTile) {
-            const uint64_t i = tile0 + e;
             Pair r[2];
             const int grp0 = e / L, j0 = e - grp0 * L;
             const U64x2 v0 = verdict[grp0];

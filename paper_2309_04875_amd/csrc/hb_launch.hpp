@@ -21,8 +21,8 @@ using BatchLauncher = hipError_t (*)(const BatchArgs &args, hipStream_t stream);
 using SimLauncher = hipError_t (*)(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t seedS,
                                    float *y, hipStream_t stream);
 
-// DReLU / ReLU among 3 or 4 parties (vec16: every buffer is 16-byte aligned).
-using MpLauncher = hipError_t (*)(const MpPointers &ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA, bool vec16,
+// DReLU / ReLU among 3 or 4 parties.
+using MpLauncher = hipError_t (*)(const MpPointers &ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
                                   hipStream_t stream);
 
 struct LauncherTable {

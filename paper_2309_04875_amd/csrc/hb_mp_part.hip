@@ -11,8 +11,7 @@
 namespace {
 
 template <int W, int P, int MODE>
-hipError_t launch_mp(const hb::MpPointers &ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA, bool vec16,
-                     hipStream_t stream)
+hipError_t launch_mp(const hb::MpPointers &ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA, hipStream_t stream)
 {
     if constexpr (hb::MpTileTraits<W, P>::kSupported) {
         if (!hb::force_group_kernel()) {
