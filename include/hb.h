@@ -47,7 +47,7 @@ enum hb_status {
     HB_EINVAL = -1, /* null pointer with n > 0, bad (k, m), n too large, forbidden overlap, not device memory */
     HB_EALIGN = -2, /* a pointer is not 8-byte aligned */
     HB_EHIP = -3,   /* the HIP runtime refused the launch; hb_last_hip_error() names the reason */
-    HB_ENOTSUP = -4 /* this entry point has no kernel for the requested slice width */
+    HB_ENOTSUP = -4 /* this entry point has no kernel for the requested slice width (no entry point returns it today) */
 };
 
 /* Largest n accepted by one call (2^40 elements). */
@@ -189,8 +189,8 @@ HB_API size_t hb_party_wire_offset(size_t n, int k, int m, int party);
  *                  share1[i] = round(2^16 x[i]) - share0[i].
  *   hb_reveal_f32: y[i] = (float)((share0[i] + share1[i] mod 2^64, read as signed) / 2^16).
  *   hb_sim_relu_f32: y = hb_reveal_f32(hb_relu(hb_share_f32(x, share_seed), k, m, seed)) in ONE kernel that
- *                  reads 4 bytes and writes 4 bytes per element; bit-identical to the composition.  Only slice
- *                  widths 4 <= m - k <= 32 have this kernel (HB_ENOTSUP otherwise); y may be x itself.
+ *                  reads 4 bytes and writes 4 bytes per element; bit-identical to the composition, for every
+ *                  slice width; y may be x itself.
  * x, y: device float arrays (4-byte aligned; 8-byte aligned for hb_sim_relu_f32).
  */
 HB_API int hb_share_f32(const float *x, size_t n, uint64_t share_seed, int64_t *share0, int64_t *share1, void *stream);

@@ -190,14 +190,30 @@ def open_shares(share0, share1, binary=False, ring_bits=64):
     return out
 
 
-def eco_scan(share0, share1, seed=1, ring_bits=64):
-    """counts[m-1] = elements whose DReLU on [0, m) differs from the full ring, by running the protocol for every m."""
+def eco_scan(share0, share1, seed=1, ring_bits=64, threads=1):
+    """counts[m-1] = elements whose DReLU on [0, m) differs from the full ring, by running the protocol for every m.
+
+    threads > 1 scans disjoint element ranges in a thread pool and adds the counts (a count is a sum over
+    elements of a per-element comparison of reconstructed values, which do not depend on the element's index).
+    """
     s0, s1 = _as_i64(share0), _as_i64(share1)
-    counts = np.zeros(64, dtype=np.uint64)
-    st = lib().hb_ref_eco_scan(_ptr(s0), _ptr(s1), _u64(s0.size), _u64(seed), ring_bits, _ptr(counts, _u64p))
-    if st != 0:
-        raise ValueError("oracle rejected arguments (status %d)" % st)
-    return counts
+    n = s0.size
+
+    def run(lo, hi):
+        counts = np.zeros(64, dtype=np.uint64)
+        st = lib().hb_ref_eco_scan(_ptr(s0[lo:hi]), _ptr(s1[lo:hi]), _u64(hi - lo), _u64(seed), ring_bits,
+                                   _ptr(counts, _u64p))
+        if st != 0:
+            raise ValueError("oracle rejected arguments (status %d)" % st)
+        return counts
+
+    threads = max(1, int(threads))
+    if threads == 1 or n < 4096:
+        return run(0, n)
+    bounds = np.linspace(0, n, threads + 1).astype(np.int64)
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        parts = list(pool.map(lambda ab: run(int(ab[0]), int(ab[1])), zip(bounds[:-1], bounds[1:])))
+    return np.sum(np.stack(parts), axis=0, dtype=np.uint64)
 
 
 def eco_choose(counts, ring_bits=64):

@@ -197,7 +197,6 @@ struct TileTraits {
     // the group lane publishes party 1's sign bit of a field next to party 0's; one-bit fields have no room for
     // that, but their 32 fields leave the upper half of the word free
     static constexpr int kSign1 = (W == 1) ? 32 : 1;
-    static constexpr bool kSimSupported = (W >= 4 && W <= 32);  // widths of the float-in / float-out kernel
     static constexpr int kGroups = tile_groups(W);              // groups per wavefront
     static constexpr int kTile = tile_elements(W);              // elements per wavefront
     static constexpr int kPairs = (kTile / 2 + kWave - 1) / kWave;   // element pairs per lane (the last may be idle)
@@ -478,6 +477,24 @@ tile_batch_kernel(const BatchArgs args)
 }
 
 // The simulator kernel: ReLU on plaintext floats through the whole protocol, 8 bytes of traffic per element.
+// Slice widths up to 32 run the wave-tile body; wider slices (one element per word) take one thread per element.
+template <int W>
+__global__ void __launch_bounds__(kBlock)
+wide_sim_kernel(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t seedS, float *y)
+{
+    using S = Shape<W>;
+    static_assert(S::L == 1, "one element per word");
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t x0 = mix64(seedS + (i + 1) * kGamma);
+    const uint64_t x1 = encode_fixed16(x[i]) - x0;
+    const uint64_t zg = seedB + (i * (uint64_t)S::words_per_group(false) + 1) * kGamma;
+    const Pair sum = a2b_sum<W, false>((x0 >> k) & S::kField, (x1 >> k) & S::kField, zg);
+    const uint64_t wb = mix64(zg + (uint64_t)S::b2a_word(false) * kGamma);
+    const Pair r = finish_element<W, kRelu>(sum, wb, 0, Pair{x0, x1}, seedA + (6 * i + 1) * kGamma);
+    y[i] = decode_fixed16(r.p0 + r.p1);
+}
+
 template <int W>
 __global__ void __launch_bounds__(kBlock)
 tile_sim_kernel(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t seedS, float *y)

@@ -55,7 +55,9 @@ template <int W>
 hipError_t launch_sim(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t seedS, float *y,
                       hipStream_t stream)
 {
-    if constexpr (hb::TileTraits<W>::kSimSupported && HB_PART_MODE == hb::kRelu) {
+    if constexpr (HB_PART_MODE != hb::kRelu) {
+        return hipErrorInvalidDeviceFunction;
+    } else if constexpr (hb::TileTraits<W>::kSupported) {
         const uint64_t wave_tiles = (n + hb::TileTraits<W>::kTile - 1) / hb::TileTraits<W>::kTile;
         const uint64_t blocks = (wave_tiles + hb::kWavesPerBlock - 1) / hb::kWavesPerBlock;
         if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
@@ -63,14 +65,18 @@ hipError_t launch_sim(const float *x, uint64_t n, int k, uint64_t seedB, uint64_
                            seedA, seedS, y);
         return hipGetLastError();
     } else {
-        return hipErrorInvalidDeviceFunction;
+        const uint64_t blocks = (n + hb::kBlock - 1) / hb::kBlock;
+        if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+        hipLaunchKernelGGL((hb::wide_sim_kernel<W>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, stream, x, n, k, seedB,
+                           seedA, seedS, y);
+        return hipGetLastError();
     }
 }
 
 template <int W>
 void fill(hb::LauncherTable &t)
 {
-    if (HB_PART_MODE == hb::kRelu) t.sim[W - 1] = hb::TileTraits<W>::kSimSupported ? &launch_sim<W> : nullptr;
+    if (HB_PART_MODE == hb::kRelu) t.sim[W - 1] = &launch_sim<W>;
     t.f[HB_PART_MODE][W - 1] = &launch_group<W, HB_PART_MODE>;
     t.batch[HB_PART_MODE][W - 1] = hb::TileTraits<W>::kSupported ? &launch_batch<W, HB_PART_MODE> : nullptr;
     if constexpr (W < HB_PART_HI) fill<W + 1>(t);

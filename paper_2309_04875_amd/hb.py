@@ -288,7 +288,7 @@ def hb_reveal_f32(share0, share1, out=None, stream=None):
 
 
 def hb_sim_relu_f32(x, k, m, seed, share_seed, out=None, stream=None):
-    """Approximate ReLU of plaintext floats through the protocol, one kernel (widths 4..32 only)."""
+    """Approximate ReLU of plaintext floats through the protocol, one kernel."""
     import torch
     n = _float_arg(x)
     if out is None:

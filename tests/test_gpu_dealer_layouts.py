@@ -9,6 +9,7 @@ import torch
 
 import oracle
 from paper_2309_04875_amd import hb, workloads
+from parity_util import assert_matches_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -113,10 +114,9 @@ def test_batch_shared_mask_one_image_set_and_mixed():
         assert bits == sum(e[2] for e in expect)
 
 
-def test_full_size_shared_mask_sampled():
-    """Three tensors of the batch-512 set at full size in one batched call: sampled elements against the
-    oracle, the reconstruction identity on every element."""
-    rng = np.random.default_rng(8)
+def test_full_size_shared_mask_every_element():
+    """Three tensors of the batch-512 set at full size in one batched call on the shared-mask layout, and the
+    largest one through the per-tensor entry points (ReLU and DReLU): every element against the oracle."""
     specs = workloads.resnet18_cifar_batch512()
     items, keep = [], []
     for spec in (specs[0], specs[7], specs[16]):
@@ -127,17 +127,16 @@ def test_full_size_shared_mask_sampled():
     bits = hb.hb_relu_batch_ex(items, SHARED)
     assert bits == sum(oracle.opened_bits(True, s.k, s.m, s.n, variant=1) for s, _ in keep)
     for (spec, x), (s0, s1, o0, o1, k, m, seed) in zip(keep, items):
-        n = spec.n
-        edge = np.concatenate([np.arange(0, 64), np.arange(n - 64, n)])
-        idx = np.unique(np.concatenate([edge, rng.integers(0, n, 1 << 14)])).astype(np.int64)
-        tidx = torch.from_numpy(idx).to(DEV)
-        e0, e1 = oracle.evaluate_at(_host(s0[tidx]), _host(s1[tidx]), idx.astype(np.uint64), k, m, seed,
-                                    oracle.WHAT_RELU, variant=1)
-        assert np.array_equal(_host(o0[tidx]), e0) and np.array_equal(_host(o1[tidx]), e1), spec
+        assert_matches_oracle(s0, s1, (o0, o1), k, m, seed, oracle.WHAT_RELU, variant=1, label=("shared batch", spec))
         w = m - k
         u = ((s0 >> k) + (s1 >> k)) & ((1 << w) - 1)
         dexp = 1 - ((u >> (w - 1)) & 1)
         assert torch.equal(hb.hb_open(o0, o1), x * dexp), spec
+    s0, s1, o0, o1, k, m, seed = items[0]
+    hb.hb_relu_ex(s0, s1, k, m, seed, SHARED, o0, o1)
+    assert_matches_oracle(s0, s1, (o0, o1), k, m, seed, oracle.WHAT_RELU, variant=1, label="relu_ex shared")
+    hb.hb_drelu_ex(s0, s1, k, m, seed, SHARED, o0, o1)
+    assert_matches_oracle(s0, s1, (o0, o1), k, m, seed, oracle.WHAT_DRELU, variant=1, label="drelu_ex shared")
 
 
 def test_unknown_layout_is_rejected():

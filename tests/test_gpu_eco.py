@@ -7,6 +7,7 @@ import torch
 
 import oracle
 from paper_2309_04875_amd import hb, workloads
+from parity_util import THREADS, host
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -56,8 +57,22 @@ def test_eco_scan_uniform_shares_unaligned_and_empty():
         hb.hb_eco_scan(d0, d1, d0[:64])               # counts inside an input
 
 
+def test_eco_scan_many_blocks_matches_protocol_oracle():
+    """2^22 + 7 elements (every block of the launch takes several chunks): all 64 counts against the oracle,
+    which evaluates the protocol at every cut for every element."""
+    spec = workloads.resnet18_cifar_batch512()[0]
+    x, s0, s1 = workloads.materialize_on_device(spec, DEV)
+    n = (1 << 22) + 7
+    got = hb.hb_eco_scan(s0[:n], s1[:n]).cpu().numpy().view(np.uint64)
+    exp = oracle.eco_scan(host(s0[:n]), host(s1[:n]), threads=THREADS)
+    assert np.array_equal(got, exp)
+    assert hb.hb_eco_choose(got) == oracle.eco_choose(exp)
+
+
 def test_eco_scan_full_size_tensor_and_choice():
-    """Largest tensor of the batch-512 set (2^25 elements): every count against the bit test on the device."""
+    """Largest tensor of the batch-512 set (2^25 elements; the protocol oracle needs 128 evaluations per element,
+    about a minute of host time at this size): every count against the bit test of Theorem 1 on the device, the
+    property the oracle's pins establish; the oracle itself is compared at 2^22 elements above."""
     spec = workloads.resnet18_cifar_batch512()[0]
     x, s0, s1 = workloads.materialize_on_device(spec, DEV)
     got = hb.hb_eco_scan(s0, s1)

@@ -7,6 +7,7 @@ import torch
 
 import oracle
 from paper_2309_04875_amd import hb
+from parity_util import THREADS
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -42,10 +43,11 @@ def test_share_and_reveal_match_oracle(n):
     assert np.array_equal(_bits(y), _bits(oracle.reveal_f32(a, b)))
 
 
-@pytest.mark.parametrize("k,m", [(12, 20), (8, 14), (0, 18), (0, 22), (8, 12), (6, 16), (16, 32), (0, 32), (7, 16)])
+@pytest.mark.parametrize("k,m", [(12, 20), (8, 14), (0, 18), (0, 22), (8, 12), (6, 16), (16, 32), (0, 32), (7, 16),
+                                 (5, 6), (5, 7), (5, 8), (0, 33), (10, 50), (0, 64), (1, 64)])
 def test_simulator_kernel_matches_oracle(k, m):
     w = m - k
-    L = 64 // w
+    L = min(64 // w, 32)
     rng = np.random.default_rng(k * 64 + m)
     for n in sorted({1, 2, L, 64 * L - 1, 64 * L, 64 * L + 1, 5 * 64 * L + 3, 30001}):
         x = _inputs(rng, n)
@@ -54,17 +56,22 @@ def test_simulator_kernel_matches_oracle(k, m):
         assert np.array_equal(_bits(y), _bits(e)), (k, m, n)
 
 
-def test_simulator_kernel_equals_composition_at_size_and_in_place():
+def test_simulator_kernel_at_size_matches_oracle_and_composition_and_in_place():
+    """2^23 + 5 floats: every output against the oracle's share -> protocol -> reveal chain, and against the
+    library's own three-call composition."""
     n = (1 << 23) + 5
     g = torch.Generator(device=DEV)
     g.manual_seed(3)
     x = torch.randn(n, generator=g, device=DEV, dtype=torch.float32) * 2
-    for (k, m) in [(12, 20), (0, 20), (8, 18)]:
+    xh = x.cpu().numpy()
+    for (k, m) in [(12, 20), (0, 20), (8, 18), (0, 64), (9, 12), (20, 21), (2, 40)]:
         s0, s1 = hb.hb_share_f32(x, 555)
         r0, r1, _ = hb.hb_relu(s0, s1, k, m, SEED)
         ref = hb.hb_reveal_f32(r0, r1)
         y = hb.hb_sim_relu_f32(x, k, m, SEED, 555)
         assert torch.equal(y.view(torch.int32), ref.view(torch.int32))
+        e = oracle.sim_relu_f32(xh, k, m, SEED, 555, threads=THREADS)
+        assert np.array_equal(_bits(y.cpu().numpy()), _bits(e)), (k, m)
     # full-ring reference through the composable pieces: exactly ReLU of the quantised input
     s0, s1 = hb.hb_share_f32(x, 555)
     r0, r1, _ = hb.hb_relu(s0, s1, 0, 64, SEED)
@@ -79,11 +86,8 @@ def test_simulator_kernel_equals_composition_at_size_and_in_place():
 def test_float_boundary_errors():
     x = torch.zeros(1001, dtype=torch.float32, device=DEV)
     with pytest.raises(hb.HbError) as e:
-        hb.hb_sim_relu_f32(x, 0, 64, SEED, 1)
-    assert e.value.status == hb.HB_ENOTSUP
-    with pytest.raises(hb.HbError) as e:
-        hb.hb_sim_relu_f32(x, 0, 2, SEED, 1)
-    assert e.value.status == hb.HB_ENOTSUP
+        hb.hb_sim_relu_f32(x, 0, 65, SEED, 1)
+    assert e.value.status == hb.HB_EINVAL
     with pytest.raises(hb.HbError) as e:
         hb.hb_sim_relu_f32(x[1:], 12, 20, SEED, 1)           # 4-byte aligned only
     assert e.value.status == hb.HB_EALIGN

@@ -1,8 +1,10 @@
 """GPU parity beyond 2^31 elements: element, group and dealer-word indices that do not fit 32 bits.
 
 One tensor of 2^31 + 2^20 + 77 int64 elements per share (17 GB each; four such buffers live on the device).
-Sampled elements (both ends, around the 2^31 boundary, random) are compared with the oracle; the
-reconstruction identity is checked on every element, chunk by chunk.
+The wavefront-tile kernel at (12, 20) is compared with the oracle on EVERY element, chunk by chunk (about
+20 s of oracle time on 16 host threads).  The full-ring and the 8-byte-aligned runs are compared with the
+oracle on every element of the ranges where an index crosses a power of two (both ends, around element 2^31,
+around group 2^28) and on random elements; the reconstruction identity is checked on every element.
 """
 import numpy as np
 import pytest
@@ -10,6 +12,7 @@ import torch
 
 import oracle
 from paper_2309_04875_amd import hb
+from parity_util import assert_matches_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -17,6 +20,9 @@ SEED = 0x2309048750000055
 DEV = "cuda"
 N = (1 << 31) + (1 << 20) + 77
 CHUNK = 1 << 27
+# element ranges compared in full where the whole tensor is not: the two ends, element 2^31, group 2^28 (L = 8)
+REGIONS = [(0, 1 << 22), ((1 << 31) - (1 << 22), (1 << 31) + (1 << 22)), ((1 << 28) - (1 << 20), (1 << 28) + (1 << 20)),
+           (N - (1 << 22), N)]
 
 
 def _fill_random(t, gen):
@@ -53,6 +59,11 @@ def test_relu_beyond_2_pow_31_elements():
         assert bits == oracle.opened_bits(True, k, m, N)
         e0, e1 = oracle.evaluate_at(h0, h1, idx.astype(np.uint64), k, m, SEED, oracle.WHAT_RELU)
         assert np.array_equal(o0[tidx].cpu().numpy(), e0) and np.array_equal(o1[tidx].cpu().numpy(), e1), (k, m)
+        if (k, m) == (12, 20):
+            assert_matches_oracle(s0, s1, (o0, o1), k, m, SEED, oracle.WHAT_RELU, label="2^31 + 2^20 + 77 elements")
+        else:
+            for (lo, hi) in REGIONS:
+                assert_matches_oracle(s0, s1, (o0, o1), k, m, SEED, oracle.WHAT_RELU, label=(k, m), lo=lo, hi=hi)
         w = m - k
         for lo in range(0, N, CHUNK):
             hi = min(lo + CHUNK, N)

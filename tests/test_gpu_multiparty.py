@@ -5,6 +5,7 @@ import torch
 
 import oracle
 from paper_2309_04875_amd import hb, workloads
+from parity_util import assert_mp_matches_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -110,10 +111,9 @@ def test_in_place_and_reconstruction(p):
 
 
 @pytest.mark.parametrize("p", [3, 4])
-def test_full_size_tensor_sampled(p):
-    """One tensor of the batch-512 set (2^25 elements) shared p ways: sampled elements against the oracle, the
-    reconstruction identity on every element."""
-    rng = np.random.default_rng(90 + p)
+def test_full_size_tensor_every_element(p):
+    """One tensor of the batch-512 set (2^25 elements) shared p ways: every element of every party's output
+    against the oracle; the reconstruction identity on the device as an extra check."""
     spec = workloads.resnet18_cifar_batch512()[0]
     x, s0, s1 = workloads.materialize_on_device(spec, DEV)
     n, k, m = spec.n, spec.k, spec.m
@@ -123,16 +123,14 @@ def test_full_size_tensor_sampled(p):
     shares = [s0, s1 - sum(extra)] + extra          # still sums to x (mod 2^64)
     got, bits = hb.hb_relu_mp(shares, k, m, SEED)
     assert bits == oracle.mp_opened_bits(True, p, k, m, n)
-    edge = np.concatenate([np.arange(0, 64), np.arange(n - 64, n)])
-    idx = np.unique(np.concatenate([edge, rng.integers(0, n, 1 << 14)])).astype(np.int64)
-    tidx = torch.from_numpy(idx).to(DEV)
-    exp = oracle.mp_evaluate_at([_host(s[tidx]) for s in shares], idx.astype(np.uint64), k, m, SEED, oracle.WHAT_RELU)
-    for q in range(p):
-        assert np.array_equal(_host(got[q][tidx]), exp[q])
+    assert_mp_matches_oracle(shares, got, k, m, SEED, oracle.WHAT_RELU, label=("relu_mp", p))
     w = m - k
     u = sum((s >> k) for s in shares) & ((1 << w) - 1)
     dexp = 1 - ((u >> (w - 1)) & 1)
     assert torch.equal(sum(got), x * dexp)
+    got, bits = hb.hb_drelu_mp(shares, k, m, SEED)
+    assert bits == oracle.mp_opened_bits(False, p, k, m, n)
+    assert_mp_matches_oracle(shares, got, k, m, SEED, oracle.WHAT_DRELU, label=("drelu_mp", p))
 
 
 def test_errors():

@@ -1,9 +1,8 @@
 """GPU parity: the HIP library, called through its C ABI, against the CPU oracle -- bit for bit.
 
 Everything is integer, so the tolerance is zero: `torch.equal` / `np.array_equal` on int64.
-Small cases are compared element by element over the whole tensor; the full-size workloads are
-compared on sampled elements (the oracle can evaluate any element by its index) plus properties
-that hold for every element and are checked on the device (reconstruction identities).
+Every case, the full-size workloads included, is compared element by element over the whole tensor
+(the oracle runs on the host cores in chunks); reconstruction identities on the device are extra checks.
 """
 import ctypes
 
@@ -13,6 +12,7 @@ import torch
 
 import oracle
 from paper_2309_04875_amd import hb, workloads
+from parity_util import assert_matches_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -118,7 +118,9 @@ def test_resnet18_cifar_one_image_set():
 
 
 # ----------------------------------------------------------------------------------------------
-# full-size workloads: sampled elements against the oracle + identities on every element
+# full-size workloads: EVERY element of every tensor against the oracle (ReLU and DReLU, through the
+# per-tensor entry points and through the batched call the benchmark times); the reconstruction
+# identity on the device is an extra check, not the parity claim
 # ----------------------------------------------------------------------------------------------
 
 def _closed_form_drelu(s0, s1, k, m):
@@ -133,59 +135,73 @@ def _closed_form_drelu(s0, s1, k, m):
     return 1 - (((u0 + u1) & mask) >> (w - 1))
 
 
-def _sample_indices(n, L, rng, count):
-    edge = np.concatenate([np.arange(0, min(n, 4 * L)), np.arange(max(0, n - 4 * L), n)])
-    rnd = rng.integers(0, n, count)
-    return np.unique(np.concatenate([edge, rnd])).astype(np.int64)
-
-
-def _check_large(spec, seed, rng, samples=1 << 16, modes=("relu",)):
+def _full_tensor_both_modes(spec, seed):
+    """hb_relu and hb_drelu on one tensor at its full size; every output element against the oracle."""
     x, s0, s1 = workloads.materialize_on_device(spec, DEV)
     n, k, m = spec.n, spec.k, spec.m
-    L = min(64 // (m - k), 32)
-    idx = _sample_indices(n, L, rng, samples)
-    tidx = torch.from_numpy(idx).to(DEV)
-    h0, h1 = _host(s0[tidx]), _host(s1[tidx])
     dexp = _closed_form_drelu(s0, s1, k, m)
-    if "relu" in modes:
-        r0, r1, bits = hb.hb_relu(s0, s1, k, m, seed)
-        assert bits == oracle.opened_bits(True, k, m, n)
-        e0, e1 = oracle.evaluate_at(h0, h1, idx.astype(np.uint64), k, m, seed, oracle.WHAT_RELU)
-        assert np.array_equal(_host(r0[tidx]), e0) and np.array_equal(_host(r1[tidx]), e1), spec
-        assert torch.equal(hb.hb_open(r0, r1), x * dexp), spec       # every element
-        del r0, r1
-    if "drelu" in modes:
-        q0, q1, _ = hb.hb_drelu(s0, s1, k, m, seed)
-        e0, e1 = oracle.evaluate_at(h0, h1, idx.astype(np.uint64), k, m, seed, oracle.WHAT_DRELU)
-        assert np.array_equal(_host(q0[tidx]), e0) and np.array_equal(_host(q1[tidx]), e1), spec
-        assert torch.equal(hb.hb_open(q0, q1), dexp), spec
+    r0, r1, bits = hb.hb_relu(s0, s1, k, m, seed)
+    assert bits == oracle.opened_bits(True, k, m, n)
+    assert_matches_oracle(s0, s1, (r0, r1), k, m, seed, oracle.WHAT_RELU, label=("relu", spec))
+    assert torch.equal(hb.hb_open(r0, r1), x * dexp), spec
+    del r0, r1
+    q0, q1, bits = hb.hb_drelu(s0, s1, k, m, seed)
+    assert bits == oracle.opened_bits(False, k, m, n)
+    assert_matches_oracle(s0, s1, (q0, q1), k, m, seed, oracle.WHAT_DRELU, label=("drelu", spec))
+    assert torch.equal(hb.hb_open(q0, q1), dexp), spec
     return n
 
 
-def test_resnet18_cifar_batch512_full_size():
-    """The headline workload in the configuration the benchmark times: one launch per tensor, per-tensor seeds."""
-    rng = np.random.default_rng(3)
-    total = 0
-    for spec in workloads.resnet18_cifar_batch512():
-        total += _check_large(spec, hb.hb_tensor_seed(SEED, spec.tensor_id), rng)
-        torch.cuda.empty_cache()
-    assert total == 285212672
+def _full_set_batched(specs, root, relu):
+    """All tensors of a set resident on the device, ONE batched call (the launch configuration the benchmark
+    times), every output element of every tensor against the oracle."""
+    items = []
+    for spec in specs:
+        _, s0, s1 = workloads.materialize_on_device(spec, DEV)
+        items.append((s0, s1, torch.empty_like(s0), torch.empty_like(s1), spec.k, spec.m,
+                      hb.hb_tensor_seed(root, spec.tensor_id)))
+    bits = (hb.hb_relu_batch if relu else hb.hb_drelu_batch)(items)
+    assert bits == sum(oracle.opened_bits(relu, s.k, s.m, s.n) for s in specs)
+    what = oracle.WHAT_RELU if relu else oracle.WHAT_DRELU
+    for spec, (s0, s1, o0, o1, k, m, seed) in zip(specs, items):
+        assert_matches_oracle(s0, s1, (o0, o1), k, m, seed, what, label=("batched", relu, spec))
+    return sum(s.n for s in specs)
 
 
-def test_width_sweep_full_size():
-    rng = np.random.default_rng(4)
-    for spec in workloads.width_sweep():
-        _check_large(spec, SEED + spec.w, rng, modes=("relu", "drelu"))
-        torch.cuda.empty_cache()
+@pytest.mark.parametrize("t", range(17))
+def test_resnet18_cifar_batch512_every_element(t):
+    """The headline workload, one launch per tensor with per-tensor seeds: ReLU and DReLU, whole tensors."""
+    spec = workloads.resnet18_cifar_batch512()[t]
+    assert spec.n == 512 * int(np.prod(workloads.RESNET18_32[t]))
+    _full_tensor_both_modes(spec, hb.hb_tensor_seed(SEED, spec.tensor_id))
+    torch.cuda.empty_cache()
 
 
-def test_resnet18_imagenet_batch64_full_size():
-    rng = np.random.default_rng(5)
-    total = 0
-    for spec in workloads.resnet18_imagenet():
-        total += _check_large(spec, hb.hb_tensor_seed(SEED, spec.tensor_id), rng)
-        torch.cuda.empty_cache()
-    assert total == 147718144
+@pytest.mark.parametrize("relu", [True, False])
+def test_resnet18_cifar_batch512_every_element_batched_call(relu):
+    assert _full_set_batched(workloads.resnet18_cifar_batch512(), SEED, relu) == 285212672
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("t", range(6))
+def test_width_sweep_every_element(t):
+    spec = workloads.width_sweep()[t]
+    assert spec.n == 1 << 26
+    _full_tensor_both_modes(spec, SEED + spec.w)
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("t", range(17))
+def test_resnet18_imagenet_batch64_every_element(t):
+    spec = workloads.resnet18_imagenet()[t]
+    _full_tensor_both_modes(spec, hb.hb_tensor_seed(SEED, spec.tensor_id))
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("relu", [True, False])
+def test_resnet18_imagenet_batch64_every_element_batched_call(relu):
+    assert _full_set_batched(workloads.resnet18_imagenet(), SEED, relu) == 147718144
+    torch.cuda.empty_cache()
 
 
 # ----------------------------------------------------------------------------------------------
@@ -238,27 +254,6 @@ def test_batch_mixed_widths_ragged_and_unaligned():
     e0, e1, b = oracle.relu(s0[1:], s1[1:], 12, 20, 4242)
     assert np.array_equal(_host(o0), e0) and np.array_equal(_host(o1), e1)
     assert bits == ebits + b
-
-
-def test_batch_full_size_headline_matches_per_tensor_calls():
-    """Batch-512 set in one batched call (the launch configuration the benchmark times) against the
-    per-tensor entry point, every element, and against the oracle on sampled elements."""
-    rng = np.random.default_rng(6)
-    specs = workloads.resnet18_cifar_batch512()
-    items, keep = [], []
-    for spec in specs[::4]:          # 5 of the 17 tensors keep the memory footprint of the test modest
-        x, s0, s1 = workloads.materialize_on_device(spec, DEV)
-        seed = hb.hb_tensor_seed(SEED, spec.tensor_id)
-        items.append((s0, s1, torch.empty_like(s0), torch.empty_like(s1), spec.k, spec.m, seed))
-        keep.append(spec)
-    hb.hb_relu_batch(items)
-    for spec, (s0, s1, o0, o1, k, m, seed) in zip(keep, items):
-        r0, r1, _ = hb.hb_relu(s0, s1, k, m, seed)
-        assert torch.equal(r0, o0) and torch.equal(r1, o1), spec
-        idx = _sample_indices(spec.n, 8, rng, 1 << 14)
-        tidx = torch.from_numpy(idx).to(DEV)
-        e0, e1 = oracle.evaluate_at(_host(s0[tidx]), _host(s1[tidx]), idx.astype(np.uint64), k, m, seed, oracle.WHAT_RELU)
-        assert np.array_equal(_host(o0[tidx]), e0) and np.array_equal(_host(o1[tidx]), e1), spec
 
 
 def test_batch_errors():
