@@ -47,7 +47,8 @@ enum hb_status {
     HB_EINVAL = -1, /* null pointer with n > 0, bad (k, m), n too large, forbidden overlap, not device memory */
     HB_EALIGN = -2, /* a pointer is not 8-byte aligned */
     HB_EHIP = -3,   /* the HIP runtime refused the launch; hb_last_hip_error() names the reason */
-    HB_ENOTSUP = -4 /* this entry point has no kernel for the requested slice width (no entry point returns it today) */
+    HB_ENOTSUP = -4, /* this entry point has no kernel for the requested slice width (no entry point returns it today) */
+    HB_ETOOBIG = -5  /* hb_relu_party_static: the call needs more workspace than the library's static array holds */
 };
 
 /* Largest n accepted by one call (2^40 elements). */
@@ -178,6 +179,25 @@ HB_API int hb_relu_party(const int64_t *share0, const int64_t *share1, size_t n,
                          int64_t *out0, int64_t *out1, void *workspace, size_t workspace_bytes,
                          uint64_t *wire_bytes, void *stream);
 HB_API size_t hb_party_workspace_bytes(size_t n, int k, int m);  /* 0 for an invalid (k, m) or n too large */
+
+/*
+ * hb_relu_party for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same result shares and the same
+ * wire traffic as hb_relu_party, but the workspace is an array of HB_PARTY_STATIC_BYTES bytes that lives inside
+ * the library's code object on every GPU the library runs on (held until the process ends).  The call allocates
+ * nothing and frees nothing; its first call on a device looks the array's device address up (once per device) --
+ * make that first call outside any stream capture.
+ *   - accepted sizes: hb_party_workspace_bytes(n, k, m) <= HB_PARTY_STATIC_BYTES (about 796,000 elements at
+ *     w = 8, 127,000 at w = 64); larger calls return HB_ETOOBIG and enqueue nothing.
+ *   - all calls on one GPU share that GPU's array: it keeps the previous call's contents (every word a call reads
+ *     it has written itself, so nothing needs clearing), and two calls whose kernels may overlap in time -- on
+ *     different streams, or from different threads -- race.  Order them on one stream or with events.
+ *   - the wires stay inside the library; wire_bytes (HOST, may be NULL) receives the bytes each party wrote.
+ * Everything else (arguments, errors, no in-place operation) is as for hb_relu_party.
+ */
+#define HB_PARTY_STATIC_BYTES ((size_t)64 << 20)
+HB_API int hb_relu_party_static(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed,
+                                int64_t *out0, int64_t *out1, uint64_t *wire_bytes, void *stream);
 HB_API size_t hb_party_wire_words(size_t n, int k, int m);
 HB_API size_t hb_party_wire_offset(size_t n, int k, int m, int party);
 

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -320,6 +321,120 @@ int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened
     return HB_OK;
 }
 
+// ---- the library's own workspace for hb_relu_party_static ---------------------------------------------------
+// One array per GPU (each device that loads the code object holds its own copy at its own address, until the
+// process ends).  In host code the array's name is only a handle for the symbol lookup below; kernels get the
+// device address that the lookup returned, as an ordinary argument.
+static __device__ __align__(256) unsigned char scratch[HB_PARTY_STATIC_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_of_device[kMaxDevices];
+
+// Device address of `scratch` on the current device; looked up once per device, with that device current.
+int party_scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return HB_EINVAL;
+    void *p = g_scratch_of_device[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_of_device[dev].store(p, std::memory_order_release);   // racing threads store the same address
+    }
+    *out = p;
+    return HB_OK;
+}
+
+// The party-faithful path on a given workspace.  `own_workspace`: the workspace is the library's static array
+// (its address and size are known good), otherwise a caller's buffer that is checked like every other argument.
+int run_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
+              int64_t *out1, void *workspace, size_t workspace_bytes, bool own_workspace, uint64_t *wire_bytes,
+              void *stream)
+{
+    int st = validate_tensor(share0, share1, n, k, m, out0, out1);
+    if (st != HB_OK) return st;
+    const PartyLayout lay = party_layout(n, k, m);
+    if (n > 0) {
+        if (workspace == nullptr || workspace_bytes < lay.total_bytes) return HB_EINVAL;
+        if (((uintptr_t)workspace & 255u) != 0) return HB_EALIGN;
+        if (!own_workspace) {
+            st = check_device_buffer(workspace, (lay.total_bytes + 7) / 8);
+            if (st != HB_OK) return st;
+        }
+        const Range ws{(uintptr_t)workspace, (uintptr_t)workspace + lay.total_bytes};
+        const Range bufs[4] = {range_of(share0, n), range_of(share1, n), range_of(out0, n), range_of(out1, n)};
+        for (const Range &b : bufs) {
+            if (!disjoint(ws, b)) return HB_EINVAL;
+        }
+        // each party re-reads its share after the other party's kernels have run: no in-place operation here
+        if (!disjoint(bufs[2], bufs[0]) || !disjoint(bufs[2], bufs[1]) || !disjoint(bufs[3], bufs[0]) ||
+            !disjoint(bufs[3], bufs[1]))
+            return HB_EINVAL;
+    }
+    if (wire_bytes) *wire_bytes = 8 * lay.wire_words;
+    if (n == 0) return HB_OK;
+
+    const int w = m - k;
+    hb::PartyShape s = {};
+    s.w = w;
+    s.R = rounds_of(w);
+    s.L = (64 / w) > 32 ? 32 : 64 / w;
+    s.k = k;
+    s.words_per_group = (uint64_t)(5 * (1 + 2 * s.R) + 1);
+    s.field = (w == 64) ? ~0ull : ((1ull << w) - 1);
+    auto repeat = [&](uint64_t f) {
+        uint64_t r = 0;
+        for (int j = 0; j < s.L; ++j) r |= f << (j * w);
+        return r;
+    };
+    s.ones = repeat(1);
+    s.live = repeat(s.field);
+    for (int r = 0; r < 6; ++r) {
+        const int sh = 1 << r;
+        s.keep[r] = (sh >= w) ? 0 : repeat((s.field << sh) & s.field);
+    }
+    s.keep1 = (1 >= w) ? 0 : repeat((s.field << 1) & s.field);
+
+    hb::PartyCtx c = {};
+    char *base = (char *)workspace;
+    c.x[0] = (const uint64_t *)share0;
+    c.x[1] = (const uint64_t *)share1;
+    c.out[0] = (uint64_t *)out0;
+    c.out[1] = (uint64_t *)out1;
+    c.n = n;
+    c.groups = lay.groups;
+    c.seedB = hb::stream_word(seed, 0);
+    c.seedA = hb::stream_word(seed, 1);
+    for (int p = 0; p < 2; ++p) {
+        c.wire[p] = (uint64_t *)(base + lay.wire_off[p]);
+        uint64_t *state = (uint64_t *)(base + lay.state_off[p]);
+        c.S[p] = state;
+        c.P[p] = state + lay.groups;
+        c.G[p] = state + 2 * lay.groups;
+        c.Z[p] = state + 3 * lay.groups;
+        c.D[p] = state + 4 * lay.groups;
+    }
+    c.off_b2a = 2 * lay.groups + 4 * lay.groups * (uint64_t)s.R;
+    c.off_mul = c.off_b2a + (n + 63) / 64;
+
+    auto grid_for = [](uint64_t threads) { return dim3((unsigned)((threads + hb::kPartyBlock - 1) / hb::kPartyBlock), 2); };
+    if ((lay.groups + hb::kPartyBlock - 1) / hb::kPartyBlock > 0x7fffffffull || (n + hb::kPartyBlock - 1) / hb::kPartyBlock > 0x7fffffffull)
+        return HB_EINVAL;
+    hipStream_t q = (hipStream_t)stream;
+    const dim3 blk(hb::kPartyBlock);
+    hipLaunchKernelGGL(hb::party_slice_kernel, grid_for(lay.groups), blk, 0, q, c, s);
+    for (int r = 0; r < s.R; ++r) hipLaunchKernelGGL(hb::party_round_kernel, grid_for(lay.groups), blk, 0, q, c, s, r);
+    hipLaunchKernelGGL(hb::party_sign_kernel, grid_for(lay.groups), blk, 0, q, c, s);
+    hipLaunchKernelGGL(hb::party_b2a_kernel, grid_for((n + 63) / 64), blk, 0, q, c, s);
+    hipLaunchKernelGGL(hb::party_mul_send_kernel, grid_for(n), blk, 0, q, c, s);
+    hipLaunchKernelGGL(hb::party_mul_finish_kernel, grid_for(n), blk, 0, q, c, s);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return HB_OK;
+}
+
 }  // namespace
 
 namespace hb {
@@ -447,84 +562,18 @@ size_t hb_party_wire_offset(size_t n, int k, int m, int party)
 int hb_relu_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
                   int64_t *out1, void *workspace, size_t workspace_bytes, uint64_t *wire_bytes, void *stream)
 {
-    int st = validate_tensor(share0, share1, n, k, m, out0, out1);
+    return run_party(share0, share1, n, k, m, seed, out0, out1, workspace, workspace_bytes, false, wire_bytes, stream);
+}
+
+int hb_relu_party_static(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed,
+                         int64_t *out0, int64_t *out1, uint64_t *wire_bytes, void *stream)
+{
+    if (!valid_slice(k, m) || n > HB_MAX_ELEMENTS) return HB_EINVAL;
+    if (party_layout(n, k, m).total_bytes > HB_PARTY_STATIC_BYTES) return HB_ETOOBIG;
+    void *ws = nullptr;
+    const int st = party_scratch_of_current_device(&ws);
     if (st != HB_OK) return st;
-    const PartyLayout lay = party_layout(n, k, m);
-    if (n > 0) {
-        if (workspace == nullptr || workspace_bytes < lay.total_bytes) return HB_EINVAL;
-        if (((uintptr_t)workspace & 255u) != 0) return HB_EALIGN;
-        st = check_device_buffer(workspace, (lay.total_bytes + 7) / 8);
-        if (st != HB_OK) return st;
-        const Range ws{(uintptr_t)workspace, (uintptr_t)workspace + lay.total_bytes};
-        const Range bufs[4] = {range_of(share0, n), range_of(share1, n), range_of(out0, n), range_of(out1, n)};
-        for (const Range &b : bufs) {
-            if (!disjoint(ws, b)) return HB_EINVAL;
-        }
-        // each party re-reads its share after the other party's kernels have run: no in-place operation here
-        if (!disjoint(bufs[2], bufs[0]) || !disjoint(bufs[2], bufs[1]) || !disjoint(bufs[3], bufs[0]) ||
-            !disjoint(bufs[3], bufs[1]))
-            return HB_EINVAL;
-    }
-    if (wire_bytes) *wire_bytes = 8 * lay.wire_words;
-    if (n == 0) return HB_OK;
-
-    const int w = m - k;
-    hb::PartyShape s = {};
-    s.w = w;
-    s.R = rounds_of(w);
-    s.L = (64 / w) > 32 ? 32 : 64 / w;
-    s.k = k;
-    s.words_per_group = (uint64_t)(5 * (1 + 2 * s.R) + 1);
-    s.field = (w == 64) ? ~0ull : ((1ull << w) - 1);
-    auto repeat = [&](uint64_t f) {
-        uint64_t r = 0;
-        for (int j = 0; j < s.L; ++j) r |= f << (j * w);
-        return r;
-    };
-    s.ones = repeat(1);
-    s.live = repeat(s.field);
-    for (int r = 0; r < 6; ++r) {
-        const int sh = 1 << r;
-        s.keep[r] = (sh >= w) ? 0 : repeat((s.field << sh) & s.field);
-    }
-    s.keep1 = (1 >= w) ? 0 : repeat((s.field << 1) & s.field);
-
-    hb::PartyCtx c = {};
-    char *base = (char *)workspace;
-    c.x[0] = (const uint64_t *)share0;
-    c.x[1] = (const uint64_t *)share1;
-    c.out[0] = (uint64_t *)out0;
-    c.out[1] = (uint64_t *)out1;
-    c.n = n;
-    c.groups = lay.groups;
-    c.seedB = hb::stream_word(seed, 0);
-    c.seedA = hb::stream_word(seed, 1);
-    for (int p = 0; p < 2; ++p) {
-        c.wire[p] = (uint64_t *)(base + lay.wire_off[p]);
-        uint64_t *state = (uint64_t *)(base + lay.state_off[p]);
-        c.S[p] = state;
-        c.P[p] = state + lay.groups;
-        c.G[p] = state + 2 * lay.groups;
-        c.Z[p] = state + 3 * lay.groups;
-        c.D[p] = state + 4 * lay.groups;
-    }
-    c.off_b2a = 2 * lay.groups + 4 * lay.groups * (uint64_t)s.R;
-    c.off_mul = c.off_b2a + (n + 63) / 64;
-
-    auto grid_for = [](uint64_t threads) { return dim3((unsigned)((threads + hb::kPartyBlock - 1) / hb::kPartyBlock), 2); };
-    if ((lay.groups + hb::kPartyBlock - 1) / hb::kPartyBlock > 0x7fffffffull || (n + hb::kPartyBlock - 1) / hb::kPartyBlock > 0x7fffffffull)
-        return HB_EINVAL;
-    hipStream_t q = (hipStream_t)stream;
-    const dim3 blk(hb::kPartyBlock);
-    hipLaunchKernelGGL(hb::party_slice_kernel, grid_for(lay.groups), blk, 0, q, c, s);
-    for (int r = 0; r < s.R; ++r) hipLaunchKernelGGL(hb::party_round_kernel, grid_for(lay.groups), blk, 0, q, c, s, r);
-    hipLaunchKernelGGL(hb::party_sign_kernel, grid_for(lay.groups), blk, 0, q, c, s);
-    hipLaunchKernelGGL(hb::party_b2a_kernel, grid_for((n + 63) / 64), blk, 0, q, c, s);
-    hipLaunchKernelGGL(hb::party_mul_send_kernel, grid_for(n), blk, 0, q, c, s);
-    hipLaunchKernelGGL(hb::party_mul_finish_kernel, grid_for(n), blk, 0, q, c, s);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail_hip(e, "kernel launch");
-    return HB_OK;
+    return run_party(share0, share1, n, k, m, seed, out0, out1, ws, HB_PARTY_STATIC_BYTES, true, wire_bytes, stream);
 }
 
 int hb_share_f32(const float *x, size_t n, uint64_t share_seed, int64_t *share0, int64_t *share1, void *stream)
@@ -702,6 +751,7 @@ const char *hb_strerror(int status)
     case HB_EALIGN: return "pointer is not 8-byte aligned";
     case HB_EHIP: return "HIP runtime error (see hb_last_hip_error)";
     case HB_ENOTSUP: return "no kernel for this slice width in this entry point";
+    case HB_ETOOBIG: return "the call needs more workspace than the library's static array holds";
     default: return "unknown status";
     }
 }

@@ -10,12 +10,13 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIBRARY = os.path.join(HERE, "libhb.so")
 
-HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP, HB_ENOTSUP = 0, -1, -2, -3, -4
+HB_OK, HB_EINVAL, HB_EALIGN, HB_EHIP, HB_ENOTSUP, HB_ETOOBIG = 0, -1, -2, -3, -4, -5
+HB_PARTY_STATIC_BYTES = 64 << 20
 HB_DEALER_PER_GATE, HB_DEALER_SHARED_MASK = 0, 1
 BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accounting
 
 EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_eco_scan", "hb_eco_choose",
-           "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
+           "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_relu_party_static", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
            "hb_drelu_ex", "hb_relu_ex", "hb_relu_batch_ex", "hb_drelu_batch_ex",
            "hb_drelu_mp", "hb_relu_mp", "hb_opened_bits_mp",
            "hb_tensor_seed", "hb_clock_probe",
@@ -80,6 +81,8 @@ def load():
     lib.hb_sim_relu_f32.argtypes = [vp, sz, ci, ci, u64, u64, vp, vp]
     lib.hb_relu_party.restype = ci
     lib.hb_relu_party.argtypes = [vp, vp, sz, ci, ci, u64, vp, vp, vp, sz, u64p, vp]
+    lib.hb_relu_party_static.restype = ci
+    lib.hb_relu_party_static.argtypes = [vp, vp, sz, ci, ci, u64, vp, vp, u64p, vp]
     lib.hb_party_workspace_bytes.restype = sz
     lib.hb_party_workspace_bytes.argtypes = [sz, ci, ci]
     lib.hb_party_wire_words.restype = sz
@@ -337,6 +340,16 @@ def hb_relu_party(share0, share1, k, m, seed, out0=None, out1=None, workspace=No
         off = hb_party_wire_offset(n, k, m, p)
         wires.append(workspace[off:off + 8 * words].view(torch.int64))
     return out0, out1, wires[0], wires[1], int(wire_bytes.value)
+
+
+def hb_relu_party_static(share0, share1, k, m, seed, out0, out1, stream=None):
+    """hb_relu_party on the library's static workspace; out0 / out1 are the caller's; returns the wire bytes per party."""
+    n = _tensor_args(share0, share1, out0, out1)
+    wire_bytes = ctypes.c_uint64(0)
+    _check(load().hb_relu_party_static(share0.data_ptr(), share1.data_ptr(), n, int(k), int(m), int(seed) & (2**64 - 1),
+                                       out0.data_ptr(), out1.data_ptr(), ctypes.byref(wire_bytes),
+                                       _stream_handle(stream)))
+    return int(wire_bytes.value)
 
 
 def hb_eco_scan(share0, share1, counts=None, stream=None):
