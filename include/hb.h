@@ -247,16 +247,6 @@ HB_API uint64_t hb_opened_bits(int relu, int k, int m, size_t n);
 /* The same count for a dealer layout: HB_DEALER_SHARED_MASK opens n * (2w + 3wR + 1) (+ 128 n).  0 for an unknown layout. */
 HB_API uint64_t hb_opened_bits_ex(int relu, int k, int m, size_t n, int dealer);
 
-/*
- * Measurement aid, not part of the protocol: the shader clock the GPU sustains while other work runs.  One
- * wavefront reads the shader-clock counter and the constant 100 MHz counter, executes `spins` iterations of a
- * short dependent arithmetic loop (bounded: it ends after exactly `spins` iterations, at most 2^20), and reads
- * both counters again.  stamps: DEVICE pointer to 2 uint64 (8-byte aligned): {shader-clock ticks, 100 MHz
- * ticks} of the loop; clock in MHz = 100 * stamps[0] / stamps[1].  Enqueue it on a stream of its own next to
- * the kernels of interest (bench.py does) to see the clock under that load.
- */
-HB_API int hb_clock_probe(uint64_t spins, uint64_t *stamps, void *stream);
-
 /* Static description of a status code. */
 HB_API const char *hb_strerror(int status);
 

@@ -1,4 +1,5 @@
-"""Build paper_2309_04875_amd/libhb.so from csrc/ with hipcc for gfx950 (cross-compiles without a GPU).
+"""Build paper_2309_04875_amd/libhb.so (the library) and libhb_probes.so (bench.py's measurement aids, a separate
+library that the product does not load) from csrc/ with hipcc for gfx950 (cross-compiles without a GPU).
 
 The group kernels exist once per (mode, slice width); hb_launch_part.hip is compiled once per mode and
 width range so that the parts build in parallel.  Objects go to a temporary directory; only the
@@ -13,6 +14,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIBRARY = os.path.join(HERE, "libhb.so")
+PROBES_LIBRARY = os.path.join(HERE, "libhb_probes.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
@@ -49,6 +51,7 @@ def build(verbose: bool = False, jobs: int = 0) -> str:
     jobs = jobs or min(8, os.cpu_count() or 1)
     work = tempfile.mkdtemp(prefix="hb_build_")
     try:
+        probes = (os.path.join(CSRC, "hb_probes.hip"), os.path.join(work, "hb_probes.o"), [])
         units = [(os.path.join(CSRC, "hb_api.hip"), os.path.join(work, "hb_api.o"), [])]
         for mode in MODES:
             for lo, hi in WIDTH_RANGES:
@@ -61,13 +64,14 @@ def build(verbose: bool = False, jobs: int = 0) -> str:
                               os.path.join(work, "mp_p%d_w%d.o" % (parties, lo)),
                               [("HB_PART_PARTIES", parties), ("HB_PART_LO", lo), ("HB_PART_HI", hi)]))
         with ThreadPoolExecutor(max_workers=jobs) as pool:
-            for out in pool.map(_compile, units):
+            for out in pool.map(_compile, [probes] + units):
                 if verbose and out.strip():
                     print(out)
-        tmp = LIBRARY + ".tmp.%d" % os.getpid()
-        cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + [u[1] for u in units] + ["-o", tmp]
-        subprocess.run(cmd, check=True)
-        os.replace(tmp, LIBRARY)
+        for objects, library in (([u[1] for u in units], LIBRARY), ([probes[1]], PROBES_LIBRARY)):
+            tmp = library + ".tmp.%d" % os.getpid()
+            cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objects + ["-o", tmp]
+            subprocess.run(cmd, check=True)
+            os.replace(tmp, library)
     finally:
         shutil.rmtree(work, ignore_errors=True)
     return LIBRARY

@@ -454,20 +454,6 @@ bool force_group_kernel()
 }
 }  // namespace hb
 
-namespace {
-__global__ void __launch_bounds__(64) clock_probe_kernel(uint64_t spins, uint64_t *stamps)
-{
-    uint64_t z = threadIdx.x;
-    const long long c0 = clock64(), w0 = wall_clock64();
-    for (uint64_t i = 0; i < spins; ++i) z = hb::mix64(z + i);
-    const long long c1 = clock64(), w1 = wall_clock64();
-    if (threadIdx.x == 0) {
-        stamps[0] = (uint64_t)(c1 - c0) + (z == 0x5bd1e995u ? 1 : 0);   // keeps the loop alive
-        stamps[1] = (uint64_t)(w1 - w0);
-    }
-}
-}  // namespace
-
 extern "C" {
 
 int hb_drelu(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
@@ -673,17 +659,6 @@ int hb_eco_scan(const int64_t *share0, const int64_t *share1, size_t n, uint64_t
     e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     return HB_OK;
-}
-
-int hb_clock_probe(uint64_t spins, uint64_t *stamps, void *stream)
-{
-    if (stamps == nullptr || spins == 0 || spins > (1ull << 20)) return HB_EINVAL;
-    if (((uintptr_t)stamps & 7u) != 0) return HB_EALIGN;
-    const int st = check_device_buffer(stamps, 2);
-    if (st != HB_OK) return st;
-    hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, spins, stamps);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? HB_OK : fail_hip(e, "kernel launch");
 }
 
 int hb_eco_choose(const uint64_t *counts)

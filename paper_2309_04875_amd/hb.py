@@ -19,7 +19,7 @@ EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", 
            "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_relu_party_static", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
            "hb_drelu_ex", "hb_relu_ex", "hb_relu_batch_ex", "hb_drelu_batch_ex",
            "hb_drelu_mp", "hb_relu_mp", "hb_opened_bits_mp",
-           "hb_tensor_seed", "hb_clock_probe",
+           "hb_tensor_seed",
            "hb_opened_bits", "hb_opened_bits_ex", "hb_strerror", "hb_last_hip_error")
 
 _lib = None
@@ -95,8 +95,6 @@ def load():
     lib.hb_eco_choose.argtypes = [u64p]
     lib.hb_open.restype = ci
     lib.hb_open.argtypes = [vp, vp, sz, ci, vp, vp]
-    lib.hb_clock_probe.restype = ci
-    lib.hb_clock_probe.argtypes = [u64, vp, vp]
     lib.hb_tensor_seed.restype = u64
     lib.hb_tensor_seed.argtypes = [u64, u64]
     lib.hb_opened_bits.restype = u64
@@ -383,17 +381,6 @@ def hb_open(share0, share1, binary=False, out=None, stream=None):
     _check(load().hb_open(share0.data_ptr(), share1.data_ptr(), n, int(bool(binary)), out.data_ptr(),
                           _stream_handle(stream)))
     return out
-
-
-def hb_clock_probe(spins, stamps=None, stream=None):
-    """Enqueue the clock probe; returns the 2-entry device tensor {shader-clock ticks, 100 MHz ticks}."""
-    import torch
-    if stamps is None:
-        stamps = torch.zeros(2, dtype=torch.int64, device="cuda")
-    if stamps.dtype != torch.int64 or stamps.numel() != 2 or not stamps.is_cuda or not stamps.is_contiguous():
-        raise TypeError("stamps must be a contiguous int64 CUDA tensor of 2 entries")
-    _check(load().hb_clock_probe(int(spins), stamps.data_ptr(), _stream_handle(stream)))
-    return stamps
 
 
 def hb_tensor_seed(root_seed, tensor_id):
