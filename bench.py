@@ -345,13 +345,20 @@ def main():
                             "elements_per_s": n / (ms * 1e-3), "hbm_frac": BYTES_PER_ELEMENT * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                             "opened_bits_per_element": bits, "kernel": kern})
 
+        # cfg 1 and cfg 2 are launch-bound: the per-call figure is the prepared-set call (hb_plan_run: arguments
+        # checked once at hb_plan_create, each call only enqueues); the plain calls, which check every pointer on
+        # every call, and a HIP-graph replay are in `extra`
         for (kk, mm) in ((0, 64), (12, 20)):                      # cfg 1: flat 65,536
             sp = workloads.flat_normal(65536, kk, mm)
             _, a, b = workloads.materialize_on_device(sp, dev)
             c, d = torch.empty_like(a), torch.empty_like(b)
+            plan = hb.hb_plan_create([(a, b, c, d, kk, mm, ROOT_SEED)], True)
+            ms = _time_launches(plan.run, torch, 30.0, 60.0)
+            add_config("cfg1 flat 65,536, (%d,%d)" % (kk, mm), sp.n, [mm - kk], "one hb_plan_run (1 launch)", ms,
+                       hb.hb_opened_bits(True, kk, mm, 1), kernel_name(mm - kk) if mm - kk > 32 else "hb::small_batch_kernel<%d, relu>" % (mm - kk))
             ms = _time_launches(lambda: hb.hb_relu(a, b, kk, mm, ROOT_SEED, c, d), torch, 30.0, 60.0)
-            add_config("cfg1 flat 65,536, (%d,%d)" % (kk, mm), sp.n, [mm - kk], "one hb_relu", ms,
-                       hb.hb_opened_bits(True, kk, mm, 1), kernel_name(mm - kk))
+            extra["flat_65536_w%d_us_plain_hb_relu_call" % (mm - kk)] = ms * 1e3
+            hb.hb_plan_destroy(plan)
         small = []                                                # cfg 2: one image, 17 tensors, per-tensor (k, m)
         for sp in workloads.resnet18_cifar():
             _, a, b = workloads.materialize_on_device(sp, dev)
@@ -359,21 +366,25 @@ def main():
         n_small = sum(t[0].numel() for t in small)
         small_batch = hb.make_batch(small)
         bits_small = hb.hb_relu_batch(small_batch) / n_small
+        plan = hb.hb_plan_create(small_batch, True)
+        ms = _time_launches(plan.run, torch, 30.0, 60.0)
+        add_config("cfg2 resnet18 32x32 one image, per-tensor (k,m)", n_small, [8], "one hb_plan_run (1 launch)", ms, bits_small,
+                   "hb::small_batch_kernel<8, relu>")
         ms = _time_launches(lambda: hb.hb_relu_batch(small_batch), torch, 30.0, 60.0)
-        add_config("cfg2 resnet18 32x32 one image, per-tensor (k,m)", n_small, [8], "one hb_relu_batch", ms, bits_small,
-                   kernel_name(8, "relu", True))
-        extra["one_image_set_us_batched_call"] = ms * 1e3
+        extra["one_image_set_us_plain_batched_call"] = ms * 1e3
         ms = _time_launches(lambda: [hb.hb_relu(a, b, kk, mm, sd, c, d) for (a, b, c, d, kk, mm, sd) in small], torch, 30.0, 60.0)
         extra["one_image_set_us_per_tensor_calls"] = ms * 1e3
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
             with torch.cuda.graph(graph, stream=side):
-                hb.hb_relu_batch(small_batch)
+                for _ in range(20):
+                    plan.run()
         torch.cuda.synchronize()
         ms = _time_launches(graph.replay, torch, 30.0, 60.0)
-        extra["one_image_set_us_graph_replay"] = ms * 1e3
-        del graph, small, small_batch
+        extra["one_image_set_us_per_call_in_a_graph_of_20"] = ms * 1e3 / 20.0
+        hb.hb_plan_destroy(plan)
+        del graph, small, small_batch, plan
         sweep = workloads.width_sweep()                           # cfg 4: flat 2^26, six widths, one pair of buffers
         _, a, b = workloads.materialize_on_device(sweep[0], dev)
         c, d = torch.empty_like(a), torch.empty_like(b)

@@ -8,7 +8,9 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <new>
 #include <utility>
+#include <vector>
 
 #include "hb_eco.hpp"
 #include "hb_float.hpp"
@@ -148,12 +150,106 @@ int mode_on(int op, int dealer)
     return -1;
 }
 
+// One kernel launch, ready to be enqueued: either a set of tensors of one width on wave-tiles (large or small) or one
+// tensor on the thread-per-group kernel.
+struct LaunchItem {
+    hb::BatchLauncher tiles = nullptr;   // wave-tile launch of args.t[0 .. args.count)
+    hb::GroupLauncher single = nullptr;  // per-tensor launch of args.t[0]
+    hb::BatchArgs args = {};
+    bool vec16 = false;
+};
+
+hipError_t enqueue(const LaunchItem &it, hipStream_t stream)
+{
+    if (it.tiles != nullptr) return it.tiles(it.args, stream);
+    const hb::BatchTensor &d = it.args.t[0];
+    return it.single(d.x0, d.x1, d.n, d.k, d.seedB, d.seedA, d.o0, d.o1, it.vec16, stream);
+}
+
+// Launches with fewer large wave-tiles than this take the small wave-tile kernels (where the width has them): below
+// about one wavefront per SIMD a launch lasts as long as one wavefront's instruction stream, which they shorten.
+// HB_SMALL_TILE_LIMIT in the environment (read once) overrides the limit; 0 switches the small tiles off.
+uint64_t small_tile_limit()
+{
+    static const uint64_t limit = [] {
+        const char *v = std::getenv("HB_SMALL_TILE_LIMIT");
+        return v != nullptr ? (uint64_t)std::strtoull(v, nullptr, 10) : (uint64_t)1536;
+    }();
+    return limit;
+}
+
+void fill_tensor(hb::BatchTensor &d, const hb_tensor &t)
+{
+    d.x0 = (const uint64_t *)t.share0;
+    d.x1 = (const uint64_t *)t.share1;
+    d.o0 = (uint64_t *)t.out0;
+    d.o1 = (uint64_t *)t.out1;
+    d.n = t.n;
+    d.seedB = hb::stream_word(t.seed, 0);
+    d.seedA = hb::stream_word(t.seed, 1);
+    d.k = t.k;
+}
+
+// Turns validated tensors (all of `mode`) into launches: tensors of one slice width that have a wave-tile kernel
+// share launches of up to kBatchMax tensors; the others get one launch each.  Tensors with n == 0 are skipped.
+// Returns HB_OK or HB_EHIP (no kernel for a width: a build problem).
+int plan_launches(int mode, const hb_tensor *tensors, size_t count, std::vector<LaunchItem> &items)
+{
+    std::vector<char> taken(count, 0);
+    for (size_t i = 0; i < count; ++i) {
+        if (taken[i]) continue;
+        taken[i] = 1;
+        const hb_tensor &first = tensors[i];
+        if (first.n == 0) continue;
+        const int w = first.m - first.k;
+        const hb::BatchLauncher big = hb::force_group_kernel() ? nullptr : hb::launcher_table().batch[mode][w - 1];
+        if (big == nullptr) {
+            LaunchItem it;
+            it.single = hb::launcher_table().f[mode][w - 1];
+            if (it.single == nullptr) return fail_hip(hipErrorInvalidDeviceFunction, "no kernel was built for this slice width");
+            fill_tensor(it.args.t[0], first);
+            it.args.count = 1;
+            const void *ptrs[4] = {first.share0, first.share1, first.out0, first.out1};
+            it.vec16 = all_aligned16(ptrs, 4);
+            items.push_back(it);
+            continue;
+        }
+        // every tensor of this width, in order
+        std::vector<size_t> same;
+        for (size_t j = i; j < count; ++j) {
+            if ((j == i || !taken[j]) && tensors[j].m - tensors[j].k == w && tensors[j].n > 0) {
+                taken[j] = 1;
+                same.push_back(j);
+            }
+        }
+        const uint64_t per_big = (uint64_t)hb::tile_elements(w);
+        uint64_t big_tiles = 0;
+        for (size_t j : same) big_tiles += (tensors[j].n + per_big - 1) / per_big;
+        const hb::BatchLauncher small = hb::launcher_table().small[mode][w - 1];
+        const bool use_small = small != nullptr && big_tiles < small_tile_limit();
+        const uint64_t per_tile = use_small ? (uint64_t)hb::small_tile_elements(w) : per_big;
+        LaunchItem it;
+        it.tiles = use_small ? small : big;
+        for (size_t j : same) {
+            if (it.args.count == hb::kBatchMax) {
+                items.push_back(it);
+                it.args = hb::BatchArgs{};
+            }
+            const hb_tensor &t = tensors[j];
+            fill_tensor(it.args.t[it.args.count], t);
+            it.args.tile_end[it.args.count] = (it.args.count ? it.args.tile_end[it.args.count - 1] : 0) + (t.n + per_tile - 1) / per_tile;
+            ++it.args.count;
+        }
+        items.push_back(it);
+    }
+    return HB_OK;
+}
+
 int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
         int64_t *out1, uint64_t *opened_bits, void *stream)
 {
     const int st = validate_tensor(share0, share1, n, k, m, out0, out1);
     if (st != HB_OK) return st;
-    const void *ptrs[4] = {share0, share1, out0, out1};
     const int w = m - k;
     uint64_t bits = 0;
     if (mode == hb::kSign) {
@@ -163,10 +259,24 @@ int run(int mode, const int64_t *share0, const int64_t *share1, size_t n, int k,
     }
     if (n > 0) {
         const uint64_t seedB = hb::stream_word(seed, 0), seedA = hb::stream_word(seed, 1);
-        const hb::GroupLauncher f = hb::launcher_table().f[mode][w - 1];
-        if (f == nullptr) return fail_hip(hipErrorInvalidDeviceFunction, "no kernel was built for this slice width");
-        const hipError_t e = f((const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, k, seedB, seedA,
-                               (uint64_t *)out0, (uint64_t *)out1, all_aligned16(ptrs, 4), (hipStream_t)stream);
+        const uint64_t per_big = (uint64_t)hb::tile_elements(w);
+        const hb::BatchLauncher small = hb::force_group_kernel() ? nullptr : hb::launcher_table().small[mode][w - 1];
+        hipError_t e;
+        if (small != nullptr && (n + per_big - 1) / per_big < small_tile_limit()) {
+            hb::BatchArgs args = {};
+            const hb_tensor t = {share0, share1, out0, out1, n, k, m, seed};
+            fill_tensor(args.t[0], t);
+            const uint64_t per_tile = (uint64_t)hb::small_tile_elements(w);
+            args.tile_end[0] = (n + per_tile - 1) / per_tile;
+            args.count = 1;
+            e = small(args, (hipStream_t)stream);
+        } else {
+            const void *ptrs[4] = {share0, share1, out0, out1};
+            const hb::GroupLauncher f = hb::launcher_table().f[mode][w - 1];
+            if (f == nullptr) return fail_hip(hipErrorInvalidDeviceFunction, "no kernel was built for this slice width");
+            e = f((const uint64_t *)share0, (const uint64_t *)share1, (uint64_t)n, k, seedB, seedA, (uint64_t *)out0,
+                  (uint64_t *)out1, all_aligned16(ptrs, 4), (hipStream_t)stream);
+        }
         if (e != hipSuccess) return fail_hip(e, "kernel launch");
     }
     if (opened_bits) *opened_bits = bits;
@@ -237,11 +347,12 @@ PartyLayout party_layout(size_t n, int k, int m)
     return lay;
 }
 
-int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
+// Argument rules of a set of tensors (no launch): each tensor's own rules, then no output of one tensor over any
+// buffer of another.  bits: the opened-bit count of the set.
+int validate_set(int mode, const hb_tensor *tensors, size_t count, uint64_t *bits)
 {
     if (count > 0 && tensors == nullptr) return HB_EINVAL;
     if (count > 4096) return HB_EINVAL;
-    // validate everything first: on error nothing is enqueued
     for (size_t i = 0; i < count; ++i) {
         const hb_tensor &t = tensors[i];
         const int st = validate_tensor(t.share0, t.share1, t.n, t.k, t.m, t.out0, t.out1);
@@ -263,59 +374,24 @@ int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened
             }
         }
     }
+    uint64_t total = 0;
+    for (size_t i = 0; i < count; ++i) total += mode_bits(mode, tensors[i].k, tensors[i].m, tensors[i].n);
+    *bits = total;
+    return HB_OK;
+}
+
+int run_batch(int mode, const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream)
+{
+    // validate everything first: on error nothing is enqueued
     uint64_t bits = 0;
-    bool taken[4096] = {};
-    for (size_t i = 0; i < count; ++i) {
-        if (taken[i]) continue;
-        const hb_tensor &first = tensors[i];
-        const int w = first.m - first.k;
-        taken[i] = true;
-        bits += mode_bits(mode, first.k, first.m, first.n);
-        if (first.n == 0) continue;
-        const hb::BatchLauncher bl = hb::launcher_table().batch[mode][w - 1];
-        if (bl == nullptr || hb::force_group_kernel()) {
-            const int st = run(mode, first.share0, first.share1, first.n, first.k, first.m, first.seed, first.out0,
-                               first.out1, nullptr, stream);
-            if (st != HB_OK) return st;
-            continue;
-        }
-        // gather the later tensors of the same width that can share the launch
-        hb::BatchArgs args = {};
-        auto add = [&](const hb_tensor &t) {
-            const uint64_t per_tile = (uint64_t)hb::tile_elements(w);
-            const uint64_t tiles = (t.n + per_tile - 1) / per_tile;
-            hb::BatchTensor &d = args.t[args.count];
-            d.x0 = (const uint64_t *)t.share0;
-            d.x1 = (const uint64_t *)t.share1;
-            d.o0 = (uint64_t *)t.out0;
-            d.o1 = (uint64_t *)t.out1;
-            d.n = t.n;
-            d.seedB = hb::stream_word(t.seed, 0);
-            d.seedA = hb::stream_word(t.seed, 1);
-            d.k = t.k;
-            args.tile_end[args.count] = (args.count ? args.tile_end[args.count - 1] : 0) + tiles;
-            ++args.count;
-        };
-        add(first);
-        auto flush = [&]() -> int {
-            if (args.count == 0) return HB_OK;
-            const hipError_t e = bl(args, (hipStream_t)stream);
-            args = hb::BatchArgs{};
-            return e == hipSuccess ? HB_OK : fail_hip(e, "kernel launch");
-        };
-        for (size_t j = i + 1; j < count; ++j) {
-            const hb_tensor &t = tensors[j];
-            if (taken[j] || t.m - t.k != w || t.n == 0) continue;
-            if (args.count == hb::kBatchMax) {
-                const int st = flush();
-                if (st != HB_OK) return st;
-            }
-            taken[j] = true;
-            bits += mode_bits(mode, t.k, t.m, t.n);
-            add(t);
-        }
-        const int st = flush();
-        if (st != HB_OK) return st;
+    int st = validate_set(mode, tensors, count, &bits);
+    if (st != HB_OK) return st;
+    std::vector<LaunchItem> items;
+    st = plan_launches(mode, tensors, count, items);
+    if (st != HB_OK) return st;
+    for (const LaunchItem &it : items) {
+        const hipError_t e = enqueue(it, (hipStream_t)stream);
+        if (e != hipSuccess) return fail_hip(e, "kernel launch");
     }
     if (opened_bits) *opened_bits = bits;
     return HB_OK;
@@ -513,6 +589,45 @@ int hb_drelu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64
     if (mode < 0) return HB_EINVAL;
     return run_batch(mode, tensors, count, opened_bits, stream);
 }
+
+struct hb_plan {
+    std::vector<LaunchItem> items;
+    uint64_t opened_bits = 0;
+};
+
+int hb_plan_create(const hb_tensor *tensors, size_t count, int relu, int dealer, hb_plan **plan)
+{
+    if (plan == nullptr) return HB_EINVAL;
+    *plan = nullptr;
+    const int mode = mode_on(relu ? hb::kRelu : hb::kDrelu, dealer);
+    if (mode < 0) return HB_EINVAL;
+    uint64_t bits = 0;
+    int st = validate_set(mode, tensors, count, &bits);
+    if (st != HB_OK) return st;
+    hb_plan *p = new (std::nothrow) hb_plan;
+    if (p == nullptr) return HB_EINVAL;
+    st = plan_launches(mode, tensors, count, p->items);
+    if (st != HB_OK) {
+        delete p;
+        return st;
+    }
+    p->opened_bits = bits;
+    *plan = p;
+    return HB_OK;
+}
+
+int hb_plan_run(const hb_plan *plan, uint64_t *opened_bits, void *stream)
+{
+    if (plan == nullptr) return HB_EINVAL;
+    for (const LaunchItem &it : plan->items) {
+        const hipError_t e = enqueue(it, (hipStream_t)stream);
+        if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    }
+    if (opened_bits) *opened_bits = plan->opened_bits;
+    return HB_OK;
+}
+
+void hb_plan_destroy(hb_plan *plan) { delete plan; }
 
 int hb_drelu_mp(const int64_t *const *shares, int parties, size_t n, int k, int m, uint64_t seed,
                 int64_t *const *outs, uint64_t *opened_bits, void *stream)

@@ -476,6 +476,161 @@ tile_batch_kernel(const BatchArgs args)
     tile_body<W, MODE>(ShareIO{d.x0, d.x1, d.o0, d.o1}, d.n, d.k, d.seedB, d.seedA, tile, lane, slices_all[wv], verdict_all[wv]);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Small wave-tile (short tensors): 16 groups per wavefront and four lanes per group.
+//
+// When a launch has fewer wave-tiles than the chip has SIMDs, its duration is one wavefront's serial instruction
+// stream (about 2000 vector instructions at w = 8), most of it dealer words.  Here a wavefront takes a quarter of
+// the elements and the four lanes of a group split the group's dealer words between them (every fourth word
+// each), hand them to one another through LDS, and all evaluate the (short) gate logic; owners then finish one
+// element pair per lane (at w = 8) instead of four.  Same dealer indices, same results; about a third of the
+// serial work per wavefront, about 1.25 times the total work, so this form is used only for launches that
+// cannot fill the chip.  Standard dealer layout, DReLU and ReLU, 4 <= w <= 32.
+// ------------------------------------------------------------------------------------------------
+template <int W>
+struct SmallTraits {
+    using S = Shape<W>;
+    using T = TileTraits<W>;
+    static constexpr int L = S::L;
+    static constexpr bool kSupported = T::kSupported && (W >= 4);
+    static constexpr int kSplit = 4;                            // lanes per group
+    static constexpr int kGroups = kWave / kSplit;              // groups per wavefront
+    static constexpr int kTile = kGroups * L;                   // elements per wavefront
+    static constexpr int kPairs = (kTile / 2 + kWave - 1) / kWave;
+    static constexpr int kWords = 10 * S::R + 1;                // evaluated dealer words of a group: 2R gates + B2A
+    static constexpr int kWordsPerLane = (kWords + kSplit - 1) / kSplit;
+    static constexpr int kStride = kWords + (kWords % 2 ? 1 : 2);     // words of LDS per group (16-byte multiple)
+    static constexpr int kSliceBytes = T::kPacked ? 2 * kGroups * 8 : kTile * (int)sizeof(typename T::Entry);
+};
+
+constexpr int small_tile_elements(int w) { return 16 * tile_lanes_per_word(w); }
+
+template <int W, int MODE, bool FULL>
+__device__ __forceinline__ void small_tile_body_impl(const ShareIO &io, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
+                                                     uint64_t tile, int lane, unsigned char *slice_lds, uint64_t *words_lds,
+                                                     U64x2 *verdict)
+{
+    using T = TileTraits<W>;
+    using Q = SmallTraits<W>;
+    using S = Shape<W>;
+    constexpr int L = Q::L;
+    static_assert(Q::kSupported && !shared_of(MODE) && op_of(MODE) != kSign, "small tiles: standard layout, DReLU / ReLU");
+    const uint64_t tile0 = tile * Q::kTile;
+
+    // ---- owners: load, slice, deposit (as in the large tile, with 16 group words per party) ----------------
+    U64x2 xa[Q::kPairs], xb[Q::kPairs];
+#pragma unroll
+    for (int c = 0; c < Q::kPairs; ++c) {
+        const int pr = c * kWave + lane;
+        const int e = 2 * pr;
+        xa[c] = U64x2{0, 0};
+        xb[c] = U64x2{0, 0};
+        if (e < Q::kTile) {
+            io.template load_pair<FULL>(tile0, (unsigned)e, n, xa[c], xb[c]);
+            if constexpr (T::kPacked) {
+                using Item = typename T::Item;
+                Item *w0 = reinterpret_cast<Item *>(slice_lds);
+                Item *w1 = reinterpret_cast<Item *>(slice_lds + Q::kGroups * 8);
+                w0[pr] = (Item)(((xa[c].a >> k) & S::kField) | (((xa[c].b >> k) & S::kField) << (W % 64)));
+                w1[pr] = (Item)(((xb[c].a >> k) & S::kField) | (((xb[c].b >> k) & S::kField) << (W % 64)));
+            } else {
+                using Entry = typename T::Entry;
+                Entry *slices = reinterpret_cast<Entry *>(slice_lds);
+                slices[e] = (Entry)((xa[c].a >> k) & S::kField) | ((Entry)((xb[c].a >> k) & S::kField) << T::kHalf);
+                slices[e + 1] = (Entry)((xa[c].b >> k) & S::kField) | ((Entry)((xb[c].b >> k) & S::kField) << T::kHalf);
+            }
+        }
+    }
+
+    // ---- every lane: its share of the group's dealer words -------------------------------------------------
+    const int grp = lane / Q::kSplit, sub = lane % Q::kSplit;
+    const uint64_t g = tile * Q::kGroups + grp;
+    const uint64_t zg = seedB + (g * (uint64_t)S::words_per_group(false) + 1) * kGamma;
+    uint64_t *gw = words_lds + grp * Q::kStride;
+#pragma unroll
+    for (int t = 0; t < Q::kWordsPerLane; ++t) {
+        const int j = t * Q::kSplit + sub;                      // j-th evaluated word: stream index j, the B2A word last
+        if (Q::kWords % Q::kSplit == 0 || t + 1 < Q::kWordsPerLane || j < Q::kWords) {
+            const unsigned idx = (j == Q::kWords - 1) ? (unsigned)S::b2a_word(false) : (unsigned)j;
+            gw[j] = mix64(zg + (uint64_t)idx * kGamma);
+        }
+    }
+    wave_sync();
+
+    // ---- every lane: collect the fields of its group, run the gate logic on the exchanged words ------------
+    uint64_t u0 = 0, u1 = 0;
+    if constexpr (T::kPacked) {
+        u0 = reinterpret_cast<const uint64_t *>(slice_lds)[grp];
+        u1 = reinterpret_cast<const uint64_t *>(slice_lds + Q::kGroups * 8)[grp];
+    } else {
+        using Entry = typename T::Entry;
+        const Entry *slices = reinterpret_cast<const Entry *>(slice_lds);
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            const Entry en = slices[grp * L + j];
+            u0 |= (uint64_t)(en & (Entry)S::kField) << (j * W);
+            u1 |= (uint64_t)(en >> T::kHalf) << (j * W);
+        }
+    }
+    const Pair sum = a2b_sum_words<W>(u0, u1, gw);
+    const uint64_t ones = S::ones();
+    const uint64_t sg = ((sum.p0 >> (W - 1)) & ones) | (((sum.p1 >> (W - 1)) & ones) << T::kSign1);
+    if (sub == 0) verdict[grp] = U64x2{sg, gw[Q::kWords - 1]};
+    wave_sync();
+
+    // ---- owners: pick up the verdict of each element's group, finish, store -------------------------------
+    const uint64_t zA0 = seedA + (6 * (tile0 + 2 * (uint64_t)lane) + 1) * kGamma;
+#pragma unroll
+    for (int c = 0; c < Q::kPairs; ++c) {
+        const int e = 2 * (c * kWave + lane);
+        if (e < Q::kTile) {
+            Pair r[2];
+            const int grp0 = e / L, j0 = e - grp0 * L;
+            const U64x2 v0 = verdict[grp0];
+            const bool split = (L % 2 != 0) && (j0 == L - 1);
+            const U64x2 v1 = split ? verdict[grp0 + 1] : v0;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const U64x2 v = h ? v1 : v0;
+                const int j = h ? (split ? 0 : j0 + 1) : j0;
+                const uint64_t sgj = v.a >> (j * W);
+                const Pair sign{sgj & 1u, (sgj >> T::kSign1) & 1u};
+                const uint32_t rh = (uint32_t)(v.b >> (2 * j));
+                const Pair rho{rh & 1u, (rh >> 1) & 1u};
+                const uint64_t zA = zA0 + (uint64_t)(6 * (2 * c * kWave + h)) * kGamma;
+                const Pair D = b2a_drelu(sign, rho, zA);
+                r[h] = (op_of(MODE) == kDrelu) ? D : beaver_mul(Pair{h ? xa[c].b : xa[c].a, h ? xb[c].b : xb[c].a}, D, zA);
+            }
+            io.template store_pair<FULL>(tile0, (unsigned)e, n, r[0], r[1]);
+        }
+    }
+}
+
+// Several tensors of one slice width on small wave-tiles; tile_end counts small tiles.
+template <int W, int MODE>
+__global__ void __launch_bounds__(kBlock)
+small_batch_kernel(const BatchArgs args)
+{
+    using T = TileTraits<W>;
+    using Q = SmallTraits<W>;
+    __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][Q::kSliceBytes];
+    __shared__ __attribute__((aligned(16))) uint64_t words_all[kWavesPerBlock][Q::kGroups * Q::kStride];
+    __shared__ U64x2 verdict_all[kWavesPerBlock][Q::kGroups + 1];
+    const int lane = threadIdx.x % kWave, wv = wave_index();
+    const uint64_t gt = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
+    if (gt >= args.tile_end[args.count - 1]) return;
+    int ti = 0;
+    while (gt >= args.tile_end[ti]) ++ti;
+    const uint64_t tile = gt - (ti ? args.tile_end[ti - 1] : 0);
+    const BatchTensor &d = args.t[ti];
+    const ShareIO io{d.x0, d.x1, d.o0, d.o1};
+    if ((tile + 1) * Q::kTile <= d.n)
+        small_tile_body_impl<W, MODE, true>(io, d.n, d.k, d.seedB, d.seedA, tile, lane, slices_all[wv], words_all[wv], verdict_all[wv]);
+    else
+        small_tile_body_impl<W, MODE, false>(io, d.n, d.k, d.seedB, d.seedA, tile, lane, slices_all[wv], words_all[wv], verdict_all[wv]);
+    (void)sizeof(T);
+}
+
 // The simulator kernel: ReLU on plaintext floats through the whole protocol, 8 bytes of traffic per element.
 // Slice widths up to 32 run the wave-tile body; wider slices (one element per word) take one thread per element.
 template <int W>

@@ -28,6 +28,7 @@ using MpLauncher = hipError_t (*)(const MpPointers &ptr, uint64_t n, int k, uint
 struct LauncherTable {
     GroupLauncher f[kModes][64];       // [mode][w - 1]
     BatchLauncher batch[kModes][64];   // null where the width has no tile kernel
+    BatchLauncher small[kModes][64];   // small wave-tiles (tile_end counts small tiles); null where there is none
     SimLauncher sim[64];               // null where the width has no tile kernel
     MpLauncher mp[kMaxParties - 2][2][64];   // [parties - 3][kDrelu | kRelu][w - 1]
 };

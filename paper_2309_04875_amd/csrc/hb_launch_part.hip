@@ -51,6 +51,22 @@ hipError_t launch_batch(const hb::BatchArgs &args, hipStream_t stream)
     }
 }
 
+constexpr bool kSmallMode = (HB_PART_MODE == hb::kDrelu || HB_PART_MODE == hb::kRelu);
+
+template <int W, int MODE>
+hipError_t launch_small_batch(const hb::BatchArgs &args, hipStream_t stream)
+{
+    if constexpr (hb::SmallTraits<W>::kSupported && kSmallMode) {
+        const uint64_t wave_tiles = args.tile_end[args.count - 1];
+        const uint64_t blocks = (wave_tiles + hb::kWavesPerBlock - 1) / hb::kWavesPerBlock;
+        if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+        hipLaunchKernelGGL((hb::small_batch_kernel<W, MODE>), dim3((unsigned)blocks), dim3(hb::kBlock), 0, stream, args);
+        return hipGetLastError();
+    } else {
+        return hipErrorInvalidDeviceFunction;
+    }
+}
+
 template <int W>
 hipError_t launch_sim(const float *x, uint64_t n, int k, uint64_t seedB, uint64_t seedA, uint64_t seedS, float *y,
                       hipStream_t stream)
@@ -79,6 +95,7 @@ void fill(hb::LauncherTable &t)
     if (HB_PART_MODE == hb::kRelu) t.sim[W - 1] = &launch_sim<W>;
     t.f[HB_PART_MODE][W - 1] = &launch_group<W, HB_PART_MODE>;
     t.batch[HB_PART_MODE][W - 1] = hb::TileTraits<W>::kSupported ? &launch_batch<W, HB_PART_MODE> : nullptr;
+    t.small[HB_PART_MODE][W - 1] = (hb::SmallTraits<W>::kSupported && kSmallMode) ? &launch_small_batch<W, HB_PART_MODE> : nullptr;
     if constexpr (W < HB_PART_HI) fill<W + 1>(t);
 }
 

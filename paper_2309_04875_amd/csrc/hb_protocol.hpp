@@ -102,13 +102,13 @@ __device__ __forceinline__ uint64_t bitop3(uint64_t a, uint64_t b, uint64_t c)
 // send, (U_0 ^ a_0) ^ (U_1 ^ a_1) = (U_0 ^ U_1) ^ (a_0 ^ a_1); the caller passes Ux = U_0 ^ U_1 and
 // Vx = (V_0 ^ V_1) before the field mask `keep` that confines a shifted operand to its field (all ones when
 // the operand is not shifted).  Party 0 takes the public d & e term.
-__device__ __forceinline__ Pair beaver_and(uint64_t zq, uint64_t Ux, uint64_t Vx, uint64_t keep, Pair acc)
+struct GateWords {   // the five dealer words of one AND gate, in stream order
+    uint64_t a0, a1, b0, b1, c0;
+};
+
+__device__ __forceinline__ Pair beaver_and_words(const GateWords &t, uint64_t Ux, uint64_t Vx, uint64_t keep, Pair acc)
 {
-    const uint64_t a0 = mix64(zq);
-    const uint64_t a1 = mix64(zq + 1 * kGamma);
-    const uint64_t b0 = mix64(zq + 2 * kGamma);
-    const uint64_t b1 = mix64(zq + 3 * kGamma);
-    const uint64_t c0 = mix64(zq + 4 * kGamma);
+    const uint64_t a0 = t.a0, a1 = t.a1, b0 = t.b0, b1 = t.b1, c0 = t.c0;
     const uint64_t a = a0 ^ a1, b = b0 ^ b1;                    // the dealer's triple (a, b, a & b)
     const uint64_t d = Ux ^ a;                                  // opened
     const uint64_t e = bitop3<kTtXorAnd>(b, Vx, keep);          // opened: (Vx & keep) ^ b
@@ -119,6 +119,17 @@ __device__ __forceinline__ Pair beaver_and(uint64_t zq, uint64_t Ux, uint64_t Vx
     const uint64_t c1 = bitop3<kTtXorAnd>(c0, a, b);
     Z.p1 = bitop3<kTtXorAnd>(bitop3<kTtXorAnd>(acc.p1 ^ c1, d, b1), e, a1);
     return Z;
+}
+
+__device__ __forceinline__ Pair beaver_and(uint64_t zq, uint64_t Ux, uint64_t Vx, uint64_t keep, Pair acc)
+{
+    GateWords t;
+    t.a0 = mix64(zq);
+    t.a1 = mix64(zq + 1 * kGamma);
+    t.b0 = mix64(zq + 2 * kGamma);
+    t.b1 = mix64(zq + 3 * kGamma);
+    t.c0 = mix64(zq + 4 * kGamma);
+    return beaver_and_words(t, Ux, Vx, keep, acc);
 }
 
 // The two Beaver ANDs of a prefix round when one mask serves their common first operand U: T = U & V, Q = U & Y.
@@ -187,6 +198,30 @@ __device__ __forceinline__ Pair a2b_sum(uint64_t u0, uint64_t u1, uint64_t zg)
             G = beaver_and(zr, Px, Gsx, keep, G);
             if (r + 1 < S::R) P = beaver_and(zr + 5 * kGamma, Px, Psx, keep, Pair{0, 0});
         }
+    }
+    const uint64_t keep1 = S::keep(1);
+    return Pair{Sum.p0 ^ ((G.p0 << 1) & keep1), Sum.p1 ^ ((G.p1 << 1) & keep1)};
+}
+
+// The same circuit on dealer words that were generated elsewhere (standard layout): words[5q + s] is slot s of
+// gate q for q = 0 .. 2R - 1 (the last round's P-update gate, q = 2R, is not evaluated and has no entry).
+template <int W>
+__device__ __forceinline__ Pair a2b_sum_words(uint64_t u0, uint64_t u1, const uint64_t *words)
+{
+    using S = Shape<W>;
+    auto gate = [&](int q) { return GateWords{words[5 * q], words[5 * q + 1], words[5 * q + 2], words[5 * q + 3], words[5 * q + 4]}; };
+    const Pair X{u0, 0}, Y{0, u1};
+    Pair P{X.p0 ^ Y.p0, X.p1 ^ Y.p1};
+    const Pair Sum = P;
+    Pair G = beaver_and_words(gate(0), X.p0 ^ X.p1, Y.p0 ^ Y.p1, ~0ull, Pair{0, 0});
+#pragma unroll
+    for (int r = 0; r < S::R; ++r) {
+        const int s = 1 << r;
+        const uint64_t keep = S::keep(s);
+        const uint64_t Px = P.p0 ^ P.p1;
+        const uint64_t Gsx = (G.p0 ^ G.p1) << s, Psx = Px << s;
+        G = beaver_and_words(gate(1 + 2 * r), Px, Gsx, keep, G);
+        if (r + 1 < S::R) P = beaver_and_words(gate(2 + 2 * r), Px, Psx, keep, Pair{0, 0});
     }
     const uint64_t keep1 = S::keep(1);
     return Pair{Sum.p0 ^ ((G.p0 << 1) & keep1), Sum.p1 ^ ((G.p1 << 1) & keep1)};

@@ -17,7 +17,7 @@ BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accountin
 
 EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_eco_scan", "hb_eco_choose",
            "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_relu_party_static", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
-           "hb_drelu_ex", "hb_relu_ex", "hb_relu_batch_ex", "hb_drelu_batch_ex",
+           "hb_drelu_ex", "hb_relu_ex", "hb_relu_batch_ex", "hb_drelu_batch_ex", "hb_plan_create", "hb_plan_run", "hb_plan_destroy",
            "hb_drelu_mp", "hb_relu_mp", "hb_opened_bits_mp",
            "hb_tensor_seed",
            "hb_opened_bits", "hb_opened_bits_ex", "hb_strerror", "hb_last_hip_error")
@@ -65,6 +65,12 @@ def load():
         f = getattr(lib, name)
         f.restype = ci
         f.argtypes = [ctypes.POINTER(hb_tensor), sz, ci, u64p, vp]
+    lib.hb_plan_create.restype = ci
+    lib.hb_plan_create.argtypes = [ctypes.POINTER(hb_tensor), sz, ci, ci, ctypes.POINTER(vp)]
+    lib.hb_plan_run.restype = ci
+    lib.hb_plan_run.argtypes = [vp, u64p, vp]
+    lib.hb_plan_destroy.restype = None
+    lib.hb_plan_destroy.argtypes = [vp]
     lib.hb_opened_bits_ex.restype = u64
     lib.hb_opened_bits_ex.argtypes = [ci, ci, ci, sz, ci]
     for name in ("hb_drelu_mp", "hb_relu_mp"):
@@ -252,6 +258,51 @@ def hb_relu_batch_ex(batch, dealer, stream=None):
 
 def hb_drelu_batch_ex(batch, dealer, stream=None):
     return _batch_call("hb_drelu_batch_ex", batch, stream, dealer)
+
+
+class Plan:
+    """Handle of hb_plan_create; keeps the tensors of the set alive.  run() enqueues the set's launches."""
+
+    def __init__(self, batch, relu=True, dealer=HB_DEALER_PER_GATE):
+        self._keep = batch
+        arr = batch if isinstance(batch, ctypes.Array) else make_batch(batch)
+        handle = ctypes.c_void_p(None)
+        _check(load().hb_plan_create(arr, len(arr), int(bool(relu)), int(dealer), ctypes.byref(handle)))
+        self._handle = handle
+        self._bits = ctypes.c_uint64(0)
+        self._run = load().hb_plan_run
+
+    def run(self, stream=None):
+        """Returns the opened bits of the set."""
+        st = self._run(self._handle, ctypes.byref(self._bits), _stream_handle(stream))
+        if st != HB_OK:
+            _check(st)
+        return self._bits.value
+
+    def close(self):
+        if self._handle is not None and self._handle.value:
+            load().hb_plan_destroy(self._handle)
+        self._handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def hb_plan_create(batch, relu=True, dealer=HB_DEALER_PER_GATE):
+    """Validate a set once (list of (share0, share1, out0, out1, k, m, seed) or a make_batch array); returns a Plan."""
+    return Plan(batch, relu, dealer)
+
+
+def hb_plan_run(plan, stream=None):
+    """Enqueue the plan's launches; returns the opened bits of the set."""
+    return plan.run(stream)
+
+
+def hb_plan_destroy(plan):
+    plan.close()
 
 
 def _float_arg(t):
