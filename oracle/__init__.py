@@ -55,6 +55,10 @@ def lib():
         L.hb_ref_wire_words.argtypes = [_u64, _int, _int]
         L.hb_ref_relu_wire.restype = _int
         L.hb_ref_relu_wire.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _u64p, _u64p]
+        L.hb_ref_wire_words_v.restype = _u64
+        L.hb_ref_wire_words_v.argtypes = [_u64, _int, _int, _int]
+        L.hb_ref_relu_wire_v.restype = _int
+        L.hb_ref_relu_wire_v.argtypes = [_i64p, _i64p, _u64, _int, _int, _u64, _int, _u64p, _u64p]
         _f32p = ctypes.POINTER(ctypes.c_float)
         L.hb_ref_share_f32.restype = _int
         L.hb_ref_share_f32.argtypes = [_f32p, _u64, _u64, _i64p, _i64p]
@@ -221,18 +225,18 @@ def eco_choose(counts, ring_bits=64):
     return int(lib().hb_ref_eco_choose(_ptr(c, _u64p), ring_bits))
 
 
-def wire_words(n, k, m):
-    return int(lib().hb_ref_wire_words(_u64(n), k, m))
+def wire_words(n, k, m, variant=0):
+    return int(lib().hb_ref_wire_words_v(_u64(n), k, m, variant))
 
 
-def relu_wire(share0, share1, k, m, seed):
+def relu_wire(share0, share1, k, m, seed, variant=0):
     """The packed words each party sends during one ReLU: (wire0, wire1) as uint64 arrays (layout in hb_ref.c)."""
     s0, s1 = _as_i64(share0), _as_i64(share1)
-    words = wire_words(s0.size, k, m)
+    words = wire_words(s0.size, k, m, variant)
     w0 = np.zeros(words, dtype=np.uint64)
     w1 = np.zeros(words, dtype=np.uint64)
-    st = lib().hb_ref_relu_wire(_ptr(s0), _ptr(s1), _u64(s0.size), k, m, _u64(seed & (2**64 - 1)),
-                                _ptr(w0, _u64p), _ptr(w1, _u64p))
+    st = lib().hb_ref_relu_wire_v(_ptr(s0), _ptr(s1), _u64(s0.size), k, m, _u64(seed & (2**64 - 1)), variant,
+                                  _ptr(w0, _u64p), _ptr(w1, _u64p))
     if st != 0:
         raise ValueError("oracle rejected arguments (status %d)" % st)
     return w0, w1

@@ -437,26 +437,36 @@ int hb_ref_eco_choose(const uint64_t *counts, int ring_bits)
 /*   multiply    : 2 words per element [2i] = x_p - a_p, [2i + 1] = DReLU_p - b_p        */
 /* Field j of a group word sits at bit j*w; bits of no element are 0.   */
 /* ------------------------------------------------------------------ */
-uint64_t hb_ref_wire_words(uint64_t n, int k, int m)
+/* Variant 1 (one mask of P per round): a round sends three words per group instead of four,           */
+/*   round r     : 3 words per group  [3g + 0] = P_p^a_p (serves both gates), [3g + 1] = (G<<s)_p^b_p   */
+/*                 of the G-update, [3g + 2] = (P<<s)_p^b'_p of the P-update.                           */
+uint64_t hb_ref_wire_words_v(uint64_t n, int k, int m, int variant)
 {
     shape_t s;
-    if (make_shape(&s, k, m, 0, 64) != HB_REF_OK) return 0;
+    if (make_shape_v(&s, k, m, 0, 64, variant) != HB_REF_OK) return 0;
     const uint64_t G = (n + (uint64_t)s.L - 1) / (uint64_t)s.L;
-    return 2 * G + 4 * G * (uint64_t)s.R + (n + 63) / 64 + 2 * n;
+    const uint64_t per_round = variant ? 3 : 4;
+    return 2 * G + per_round * G * (uint64_t)s.R + (n + 63) / 64 + 2 * n;
 }
 
-int hb_ref_relu_wire(const int64_t *share0, const int64_t *share1, uint64_t n, int k, int m, uint64_t seed,
-                     uint64_t *wire0, uint64_t *wire1)
+uint64_t hb_ref_wire_words(uint64_t n, int k, int m)
+{
+    return hb_ref_wire_words_v(n, k, m, 0);
+}
+
+int hb_ref_relu_wire_v(const int64_t *share0, const int64_t *share1, uint64_t n, int k, int m, uint64_t seed,
+                       int variant, uint64_t *wire0, uint64_t *wire1)
 {
     shape_t s;
     uint64_t i, words;
     int p, r;
-    if (make_shape(&s, k, m, seed, 64) != HB_REF_OK) return HB_REF_EINVAL;
+    if (make_shape_v(&s, k, m, seed, 64, variant) != HB_REF_OK) return HB_REF_EINVAL;
     if (n > 0 && (!share0 || !share1 || !wire0 || !wire1)) return HB_REF_EINVAL;
-    words = hb_ref_wire_words(n, k, m);
+    words = hb_ref_wire_words_v(n, k, m, variant);
     for (i = 0; i < words; i++) wire0[i] = wire1[i] = 0;
     const uint64_t G = (n + (uint64_t)s.L - 1) / (uint64_t)s.L;
-    const uint64_t off_b2a = 2 * G + 4 * G * (uint64_t)s.R, off_mul = off_b2a + (n + 63) / 64;
+    const uint64_t per_round = variant ? 3 : 4;
+    const uint64_t off_b2a = 2 * G + per_round * G * (uint64_t)s.R, off_mul = off_b2a + (n + 63) / 64;
     for (i = 0; i < n; i++) {
         elem_t t;
         uint64_t *wire[2] = { wire0, wire1 };
@@ -467,11 +477,18 @@ int hb_ref_relu_wire(const int64_t *share0, const int64_t *share1, uint64_t n, i
             wire[p][2 * g + 0] |= t.send_d[p][0] << sh;
             wire[p][2 * g + 1] |= t.send_e[p][0] << sh;
             for (r = 0; r < s.R; r++) {
-                uint64_t *sec = wire[p] + 2 * G + 4 * G * (uint64_t)r;
-                sec[4 * g + 0] |= t.send_d[p][1 + 2 * r] << sh;
-                sec[4 * g + 1] |= t.send_e[p][1 + 2 * r] << sh;
-                sec[4 * g + 2] |= t.send_d[p][2 + 2 * r] << sh;
-                sec[4 * g + 3] |= t.send_e[p][2 + 2 * r] << sh;
+                uint64_t *sec = wire[p] + 2 * G + per_round * G * (uint64_t)r;
+                if (variant) {
+                    /* the masked P is the same message for both gates of the round: sent once */
+                    sec[3 * g + 0] |= t.send_d[p][1 + 2 * r] << sh;
+                    sec[3 * g + 1] |= t.send_e[p][1 + 2 * r] << sh;
+                    sec[3 * g + 2] |= t.send_e[p][2 + 2 * r] << sh;
+                } else {
+                    sec[4 * g + 0] |= t.send_d[p][1 + 2 * r] << sh;
+                    sec[4 * g + 1] |= t.send_e[p][1 + 2 * r] << sh;
+                    sec[4 * g + 2] |= t.send_d[p][2 + 2 * r] << sh;
+                    sec[4 * g + 3] |= t.send_e[p][2 + 2 * r] << sh;
+                }
             }
             wire[p][off_b2a + i / 64] |= t.send_z[p] << (i % 64);
             wire[p][off_mul + 2 * i + 0] = t.send_eps[p];
@@ -479,6 +496,12 @@ int hb_ref_relu_wire(const int64_t *share0, const int64_t *share1, uint64_t n, i
         }
     }
     return HB_REF_OK;
+}
+
+int hb_ref_relu_wire(const int64_t *share0, const int64_t *share1, uint64_t n, int k, int m, uint64_t seed,
+                     uint64_t *wire0, uint64_t *wire1)
+{
+    return hb_ref_relu_wire_v(share0, share1, n, k, m, seed, 0, wire0, wire1);
 }
 
 /* ------------------------------------------------------------------ */

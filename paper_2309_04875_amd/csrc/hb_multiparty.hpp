@@ -9,9 +9,9 @@
 //   - an element owns 4P - 2 arithmetic words: rA_0..rA_{P-2} | a_0..a_{P-1} | b_0..b_{P-1} | c_0..c_{P-2};
 //   - party 0 adds every public term.
 //
-//   mp_group_kernel   one thread per group, scalar 8-byte accesses: the remaining widths.
-//   mp_tile_kernel    one wavefront per 64 groups with coalesced 16-byte accesses, as tile_kernel: slice
-//                     widths 4..32.
+//   mp_group_kernel   one thread per group, scalar 8-byte accesses: slice widths above 32.
+//   mp_tile_kernel    one wavefront per 64 groups (32 below w = 4, where a group has 16 or 21 elements) with
+//                     coalesced 16-byte accesses, as tile_kernel: slice widths up to 32.
 //
 // Algorithmic traffic: 16 P bytes per element.
 #pragma once
@@ -236,14 +236,17 @@ mp_group_kernel(const MpPointers ptr, uint64_t n, uint64_t groups, int k, uint64
 
 // Tile kernel among P parties: the owner / group-lane scheme of tile_body.  LDS per wavefront: P arrays of one
 // entry (1, 2 or 4 bytes) per element for the slices, and per group {sign shares, B2A word}; the sign share of
-// party q for lane j sits at bit j*W + q (W >= 4 >= P).
+// party q for lane j sits at bit j*W + q when a field has room for P bits (W >= P); narrower fields publish one
+// word per party instead (the sum word itself: the sign of lane j is bit j*W + W - 1).
 template <int W, int P>
 struct MpTileTraits {
     using M = MpShape<W, P>;
     static constexpr int L = M::L;
-    static constexpr bool kSupported = (W >= 4 && W <= 32);      // then L = 64 / W, between 2 and 16
-    static constexpr int kTile = kWave * L;
-    static constexpr int kPairs = (L + 1) / 2;
+    static constexpr bool kSupported = (W <= 32);
+    static constexpr int kGroups = (W >= 4) ? kWave : kWave / 2;   // half the lanes run the circuit when L > 16:
+    static constexpr int kTile = kGroups * L;                      // a lane then owns at most 6 element pairs
+    static constexpr int kPairs = (kTile / 2 + kWave - 1) / kWave;
+    static constexpr bool kSignWords = (W < P);
     using Entry = typename std::conditional<(W <= 8), uint8_t,
                   typename std::conditional<(W <= 16), uint16_t, uint32_t>::type>::type;
     static constexpr bool kWordIsPacked = (int)sizeof(Entry) * 8 == W;   // the L entries of a group are its SWAR word
@@ -255,7 +258,7 @@ struct MpTileTraits {
 template <int W, int P, int MODE, bool FULL>
 __device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA,
                                              uint64_t tile, int lane, unsigned char (*slice_lds)[MpTileTraits<W, P>::kSliceBytes],
-                                             U64x2 *verdict)
+                                             U64x2 *verdict, uint64_t (*sign_words)[P])
 {
     using S = Shape<W>;
     using M = MpShape<W, P>;
@@ -289,26 +292,31 @@ __device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, uint64_t n, 
     wave_sync();
 
     // ---- group lanes: collect the fields of group `lane`, run the adder tree, publish signs and B2A word
-    uint64_t u[P];
+    if (T::kGroups == kWave || lane < T::kGroups) {
+        uint64_t u[P];
 #pragma unroll
-    for (int q = 0; q < P; ++q) {
-        if constexpr (T::kWordIsPacked) {
-            u[q] = reinterpret_cast<const uint64_t *>(slice_lds[q])[lane];
-        } else {
-            const Entry *sl = reinterpret_cast<const Entry *>(slice_lds[q]);
-            u[q] = 0;
+        for (int q = 0; q < P; ++q) {
+            if constexpr (T::kWordIsPacked) {
+                u[q] = reinterpret_cast<const uint64_t *>(slice_lds[q])[lane];
+            } else {
+                const Entry *sl = reinterpret_cast<const Entry *>(slice_lds[q]);
+                u[q] = 0;
 #pragma unroll
-            for (int j = 0; j < L; ++j) u[q] |= (uint64_t)sl[lane * L + j] << (j * W);
+                for (int j = 0; j < L; ++j) u[q] |= (uint64_t)sl[lane * L + j] << (j * W);
+            }
         }
-    }
-    const uint64_t g = tile * kWave + lane;
-    const uint64_t zg = seedB + (g * (uint64_t)M::kWordsPerGroup + 1) * kGamma;
-    const Shares<P> sum = mp_a2b_sum<W, P>(u, zg);
-    {
+        const uint64_t g = tile * T::kGroups + lane;
+        const uint64_t zg = seedB + (g * (uint64_t)M::kWordsPerGroup + 1) * kGamma;
+        const Shares<P> sum = mp_a2b_sum<W, P>(u, zg);
         const uint64_t ones = S::ones();
         uint64_t sg = 0;
+        if constexpr (T::kSignWords) {
 #pragma unroll
-        for (int q = 0; q < P; ++q) sg |= ((sum.v[q] >> (W - 1)) & ones) << q;
+            for (int q = 0; q < P; ++q) sign_words[lane][q] = sum.v[q];
+        } else {
+#pragma unroll
+            for (int q = 0; q < P; ++q) sg |= ((sum.v[q] >> (W - 1)) & ones) << q;
+        }
         verdict[lane] = U64x2{sg, mix64(zg + (uint64_t)M::kB2aWord * kGamma)};
     }
     wave_sync();
@@ -328,7 +336,15 @@ __device__ __forceinline__ void mp_tile_body(const MpPointers &ptr, uint64_t n, 
             for (int h = 0; h < 2; ++h) {
                 const U64x2 v = h ? v1 : v0;
                 const int j = h ? (split ? 0 : j0 + 1) : j0;
-                const uint32_t sign = (uint32_t)(v.a >> (j * W)) & ((1u << P) - 1);
+                uint32_t sign;
+                if constexpr (T::kSignWords) {
+                    const int gj = h ? (split ? grp0 + 1 : grp0) : grp0;
+                    sign = 0;
+#pragma unroll
+                    for (int q = 0; q < P; ++q) sign |= ((uint32_t)(sign_words[gj][q] >> (j * W + W - 1)) & 1u) << q;
+                } else {
+                    sign = (uint32_t)(v.a >> (j * W)) & ((1u << P) - 1);
+                }
                 const uint32_t rho = (uint32_t)(v.b >> (P * j)) & ((1u << P) - 1);
                 Shares<P> x;
 #pragma unroll
@@ -354,16 +370,17 @@ __global__ void __launch_bounds__(kBlock)
 mp_tile_kernel(const MpPointers ptr, uint64_t n, int k, uint64_t seedB, uint64_t seedA)
 {
     using T = MpTileTraits<W, P>;
-    static_assert(T::kSupported, "tile kernel needs 4 <= W <= 32");
+    static_assert(T::kSupported, "tile kernel needs W <= 32");
     __shared__ __attribute__((aligned(16))) unsigned char slices_all[kWavesPerBlock][P][T::kSliceBytes];
     __shared__ U64x2 verdict_all[kWavesPerBlock][kWave];
+    __shared__ uint64_t sign_words_all[kWavesPerBlock][T::kSignWords ? kWave : 1][P];
     const int lane = threadIdx.x % kWave, wv = wave_index();
     const uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wv;
     if (tile * T::kTile >= n) return;        // whole wavefront beyond the tensor
     if ((tile + 1) * T::kTile <= n)
-        mp_tile_body<W, P, MODE, true>(ptr, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+        mp_tile_body<W, P, MODE, true>(ptr, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv], sign_words_all[wv]);
     else
-        mp_tile_body<W, P, MODE, false>(ptr, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv]);
+        mp_tile_body<W, P, MODE, false>(ptr, n, k, seedB, seedA, tile, lane, slices_all[wv], verdict_all[wv], sign_words_all[wv]);
 }
 
 }  // namespace hb

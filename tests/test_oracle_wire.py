@@ -17,11 +17,27 @@ import oracle
 M64 = (1 << 64) - 1
 
 
-def _shape(k, m):
+def _shape(k, m, variant=0):
     w = m - k
     R = 0 if w == 1 else (w - 1).bit_length()
     L = min(64 // w, 32)
-    return w, R, L, 5 * (1 + 2 * R) + 1
+    return w, R, L, (5 + 8 * R + 1) if variant else (5 * (1 + 2 * R) + 1)
+
+
+def _dealer_word(variant, R, gate, slot):
+    """Index, inside a group's dealer words, of slot (0: a_0, 1: a_1, 2: b_0, 3: b_1, 4: c_0) of a gate
+    (0: gate 0; ("T", r) / ("P", r): the G-update / P-update of round r), written out from the protocol text.
+    Shared-mask layout: gate 0 owns words 0..4; round r owns 5 + 8r .. 5 + 8r + 7 =
+    a_0 a_1 | b_0 b_1 c_0 (G-update) | b_0 b_1 c_0 (P-update)."""
+    if gate == 0:
+        return slot
+    kind, r = gate
+    if not variant:
+        return 5 * ((1 if kind == "T" else 2) + 2 * r) + slot
+    base = 5 + 8 * r
+    if slot < 2:
+        return base + slot
+    return base + (2 if kind == "T" else 5) + (slot - 2)
 
 
 def _window_generate(u0, u1, lo, hi):
@@ -41,29 +57,31 @@ def _window_propagate(u0, u1, lo, hi):
     return 1 if ((p >> lo) & ((1 << width) - 1)) == (1 << width) - 1 else 0
 
 
+@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("k,m", [(12, 20), (0, 64), (8, 14), (8, 18), (3, 4), (0, 2), (5, 12), (20, 53), (8, 12), (0, 33)])
-def test_openings_unmask_to_kogge_stone_state(k, m):
-    w, R, L, Wg = _shape(k, m)
+def test_openings_unmask_to_kogge_stone_state(k, m, variant):
+    w, R, L, Wg = _shape(k, m, variant)
+    per_round = 3 if variant else 4
     rng = np.random.default_rng(k * 64 + m)
     n = 2 * L + max(1, L // 2)
     s0 = rng.integers(0, 1 << 64, n, dtype=np.uint64).view(np.int64)
     s1 = rng.integers(0, 1 << 64, n, dtype=np.uint64).view(np.int64)
     seed = 0xABCDEF + m
-    w0, w1 = oracle.relu_wire(s0, s1, k, m, seed)
+    w0, w1 = oracle.relu_wire(s0, s1, k, m, seed, variant)
     w0 = [int(v) for v in w0]
     w1 = [int(v) for v in w1]
     G = (n + L - 1) // L
-    assert len(w0) == 2 * G + 4 * G * R + (n + 63) // 64 + 2 * n == oracle.wire_words(n, k, m)
+    assert len(w0) == 2 * G + per_round * G * R + (n + 63) // 64 + 2 * n == oracle.wire_words(n, k, m, variant)
     seedB, seedA = oracle.sm(seed, 0), oracle.sm(seed, 1)
     mask = (1 << w) - 1
-    d0, d1, _ = oracle.drelu(s0, s1, k, m, seed)
+    d0, d1, _ = oracle.drelu(s0, s1, k, m, seed, variant=variant)
     for i in range(n):
         g, j = divmod(i, L)
         x0, x1 = int(s0[i]) & M64, int(s1[i]) & M64
         u0, u1 = (x0 >> k) & mask, (x1 >> k) & mask
 
-        def dealer(q, slot):
-            return (oracle.sm(seedB, g * Wg + 5 * q + slot) >> (j * w)) & mask
+        def dealer(gate, slot):
+            return (oracle.sm(seedB, g * Wg + _dealer_word(variant, R, gate, slot)) >> (j * w)) & mask
 
         def opened(section_off, per_group, idx):
             pos = section_off + per_group * g + idx
@@ -74,18 +92,24 @@ def test_openings_unmask_to_kogge_stone_state(k, m):
         assert opened(0, 2, 1) ^ dealer(0, 2) ^ dealer(0, 3) == u1
         for r in range(R):
             s = 1 << r
-            off = 2 * G + 4 * G * r
+            off = 2 * G + per_round * G * r
             P = sum(_window_propagate(u0, u1, b - s + 1, b) << b for b in range(w))
             Gn = sum(_window_generate(u0, u1, b - s + 1, b) << b for b in range(w))
-            qT, qP = 1 + 2 * r, 2 + 2 * r
-            assert opened(off, 4, 0) ^ dealer(qT, 0) ^ dealer(qT, 1) == P, (i, r)
-            assert opened(off, 4, 1) ^ dealer(qT, 2) ^ dealer(qT, 3) == (Gn << s) & mask, (i, r)
-            assert opened(off, 4, 2) ^ dealer(qP, 0) ^ dealer(qP, 1) == P, (i, r)
-            assert opened(off, 4, 3) ^ dealer(qP, 2) ^ dealer(qP, 3) == (P << s) & mask, (i, r)
+            qT, qP = ("T", r), ("P", r)
+            if variant:     # P ^ a travels once and serves both gates
+                assert opened(off, 3, 0) ^ dealer(qT, 0) ^ dealer(qT, 1) == P, (i, r)
+                assert dealer(qP, 0) == dealer(qT, 0) and dealer(qP, 1) == dealer(qT, 1)
+                assert opened(off, 3, 1) ^ dealer(qT, 2) ^ dealer(qT, 3) == (Gn << s) & mask, (i, r)
+                assert opened(off, 3, 2) ^ dealer(qP, 2) ^ dealer(qP, 3) == (P << s) & mask, (i, r)
+            else:
+                assert opened(off, 4, 0) ^ dealer(qT, 0) ^ dealer(qT, 1) == P, (i, r)
+                assert opened(off, 4, 1) ^ dealer(qT, 2) ^ dealer(qT, 3) == (Gn << s) & mask, (i, r)
+                assert opened(off, 4, 2) ^ dealer(qP, 0) ^ dealer(qP, 1) == P, (i, r)
+                assert opened(off, 4, 3) ^ dealer(qP, 2) ^ dealer(qP, 3) == (P << s) & mask, (i, r)
         # B2A: the opened bit is the sign masked by the dealer's bit
-        off_b = 2 * G + 4 * G * R
+        off_b = 2 * G + per_round * G * R
         z = ((w0[off_b + i // 64] ^ w1[off_b + i // 64]) >> (i % 64)) & 1
-        wb = oracle.sm(seedB, g * Wg + 5 * (1 + 2 * R))
+        wb = oracle.sm(seedB, g * Wg + Wg - 1)
         rbit = ((wb >> (2 * j)) ^ (wb >> (2 * j + 1))) & 1
         sign = ((u0 + u1) >> (w - 1)) & 1
         assert z ^ rbit == sign
@@ -100,7 +124,8 @@ def test_openings_unmask_to_kogge_stone_state(k, m):
     # bits that belong to no element are zero (dead top bits of a word, fields past n in the last group)
     used = n - (G - 1) * L
     live_last = (1 << (used * w)) - 1
-    for pos in [2 * (G - 1), 2 * (G - 1) + 1] + [2 * G + 4 * G * r + 4 * (G - 1) + t for r in range(R) for t in range(4)]:
+    for pos in [2 * (G - 1), 2 * (G - 1) + 1] + [2 * G + per_round * G * r + per_round * (G - 1) + t
+                                                for r in range(R) for t in range(per_round)]:
         assert w0[pos] & ~live_last & M64 == 0 and w1[pos] & ~live_last & M64 == 0
     if n % 64:
         tail = off_b + (n + 63) // 64 - 1
@@ -112,6 +137,8 @@ def test_wire_size_is_the_opened_bit_count():
     for (k, m) in [(12, 20), (8, 12), (0, 16), (4, 36), (0, 64), (9, 11)]:
         for n in (64, 640, 4096):
             assert 64 * oracle.wire_words(n, k, m) == oracle.opened_bits(True, k, m, n)
+            # one mask of P per round: three words per round instead of four, 3w opened bits instead of 4w
+            assert 64 * oracle.wire_words(n, k, m, 1) == oracle.opened_bits(True, k, m, n, variant=1)
     # otherwise the only excess is padding: dead top bits of group words, the ragged last group, the last B2A word
     for (k, m, n) in [(8, 14, 1000), (8, 18, 1000), (12, 20, 1001), (0, 33, 77), (5, 6, 64), (5, 6, 100)]:
         w, R, L, _ = _shape(k, m)
