@@ -219,6 +219,21 @@ HB_API size_t hb_party_wire_words(size_t n, int k, int m);
 HB_API size_t hb_party_wire_offset(size_t n, int k, int m, int party);
 
 /*
+ * The same on a dealer layout (`dealer` as for hb_relu_ex; HB_DEALER_PER_GATE is hb_relu_party bit for bit).  On
+ * HB_DEALER_SHARED_MASK the two gates of a prefix round share the mask of P, so each party sends P ^ a once: a round
+ * occupies three wire words per group, [3g] the masked P, [3g + 1] the masked second operand of the G-update,
+ * [3g + 2] that of the P-update, and the wire is [2G][3G per round, R rounds][ceil(n/64)][2n] words -- 64 x words =
+ * hb_opened_bits_ex(1, k, m, n, HB_DEALER_SHARED_MASK) when w*L = 64 and 64 divides n.  Result shares equal
+ * hb_relu_ex's for that layout.  The *_ex size queries return 0 for an unknown layout.
+ */
+HB_API int hb_relu_party_ex(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed,
+                            int dealer, int64_t *out0, int64_t *out1, void *workspace, size_t workspace_bytes,
+                            uint64_t *wire_bytes, void *stream);
+HB_API size_t hb_party_workspace_bytes_ex(size_t n, int k, int m, int dealer);
+HB_API size_t hb_party_wire_words_ex(size_t n, int k, int m, int dealer);
+HB_API size_t hb_party_wire_offset_ex(size_t n, int k, int m, int dealer, int party);
+
+/*
  * Float boundary of the single-node simulator (Sec. 4.1.1: floating-point activations are converted to ring
  * elements, shared, and the ReLU layer is evaluated by the protocol).  Fixed point is x = round(2^16 x_f), ties
  * to even (Sec. 2.2, Sec. 3.1); NaN encodes as 0 and |2^16 x_f| is clamped to 2^62.

@@ -329,14 +329,15 @@ struct PartyLayout {
     uint64_t groups, wire_words, wire_off[2], state_off[2], total_bytes;
 };
 
-PartyLayout party_layout(size_t n, int k, int m)
+PartyLayout party_layout(size_t n, int k, int m, int dealer = HB_DEALER_PER_GATE)
 {
     const int w = m - k;
     const uint64_t L = (64 / w) > 32 ? 32 : (uint64_t)(64 / w);
     const uint64_t R = (uint64_t)rounds_of(w);
+    const uint64_t per_round = dealer == HB_DEALER_SHARED_MASK ? 3 : 4;
     PartyLayout lay = {};
     lay.groups = ((uint64_t)n + L - 1) / L;
-    lay.wire_words = 2 * lay.groups + 4 * lay.groups * R + ((uint64_t)n + 63) / 64 + 2 * (uint64_t)n;
+    lay.wire_words = 2 * lay.groups + per_round * lay.groups * R + ((uint64_t)n + 63) / 64 + 2 * (uint64_t)n;
     auto up = [](uint64_t b) { return (b + 255) & ~255ull; };
     const uint64_t wire_bytes = up(8 * lay.wire_words), state_bytes = up(8 * (4 * lay.groups + (uint64_t)n));
     lay.wire_off[0] = 0;
@@ -425,13 +426,14 @@ int party_scratch_of_current_device(void **out)
 
 // The party-faithful path on a given workspace.  `own_workspace`: the workspace is the library's static array
 // (its address and size are known good), otherwise a caller's buffer that is checked like every other argument.
-int run_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
-              int64_t *out1, void *workspace, size_t workspace_bytes, bool own_workspace, uint64_t *wire_bytes,
-              void *stream)
+int run_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int dealer,
+              int64_t *out0, int64_t *out1, void *workspace, size_t workspace_bytes, bool own_workspace,
+              uint64_t *wire_bytes, void *stream)
 {
+    if (dealer != HB_DEALER_PER_GATE && dealer != HB_DEALER_SHARED_MASK) return HB_EINVAL;
     int st = validate_tensor(share0, share1, n, k, m, out0, out1);
     if (st != HB_OK) return st;
-    const PartyLayout lay = party_layout(n, k, m);
+    const PartyLayout lay = party_layout(n, k, m, dealer);
     if (n > 0) {
         if (workspace == nullptr || workspace_bytes < lay.total_bytes) return HB_EINVAL;
         if (((uintptr_t)workspace & 255u) != 0) return HB_EALIGN;
@@ -458,7 +460,9 @@ int run_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int
     s.R = rounds_of(w);
     s.L = (64 / w) > 32 ? 32 : 64 / w;
     s.k = k;
-    s.words_per_group = (uint64_t)(5 * (1 + 2 * s.R) + 1);
+    s.shared = dealer == HB_DEALER_SHARED_MASK;
+    s.per_round = s.shared ? 3 : 4;
+    s.words_per_group = (uint64_t)(s.shared ? 5 + 8 * s.R + 1 : 5 * (1 + 2 * s.R) + 1);
     s.field = (w == 64) ? ~0ull : ((1ull << w) - 1);
     auto repeat = [&](uint64_t f) {
         uint64_t r = 0;
@@ -492,7 +496,7 @@ int run_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int
         c.Z[p] = state + 3 * lay.groups;
         c.D[p] = state + 4 * lay.groups;
     }
-    c.off_b2a = 2 * lay.groups + 4 * lay.groups * (uint64_t)s.R;
+    c.off_b2a = 2 * lay.groups + (uint64_t)s.per_round * lay.groups * (uint64_t)s.R;
     c.off_mul = c.off_b2a + (n + 63) / 64;
 
     auto grid_for = [](uint64_t threads) { return dim3((unsigned)((threads + hb::kPartyBlock - 1) / hb::kPartyBlock), 2); };
@@ -663,7 +667,36 @@ size_t hb_party_wire_offset(size_t n, int k, int m, int party)
 int hb_relu_party(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int64_t *out0,
                   int64_t *out1, void *workspace, size_t workspace_bytes, uint64_t *wire_bytes, void *stream)
 {
-    return run_party(share0, share1, n, k, m, seed, out0, out1, workspace, workspace_bytes, false, wire_bytes, stream);
+    return run_party(share0, share1, n, k, m, seed, HB_DEALER_PER_GATE, out0, out1, workspace, workspace_bytes, false,
+                     wire_bytes, stream);
+}
+
+int hb_relu_party_ex(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed, int dealer,
+                     int64_t *out0, int64_t *out1, void *workspace, size_t workspace_bytes, uint64_t *wire_bytes,
+                     void *stream)
+{
+    return run_party(share0, share1, n, k, m, seed, dealer, out0, out1, workspace, workspace_bytes, false, wire_bytes,
+                     stream);
+}
+
+size_t hb_party_wire_words_ex(size_t n, int k, int m, int dealer)
+{
+    if (!valid_slice(k, m) || n > HB_MAX_ELEMENTS || (dealer != HB_DEALER_PER_GATE && dealer != HB_DEALER_SHARED_MASK)) return 0;
+    return (size_t)party_layout(n, k, m, dealer).wire_words;
+}
+
+size_t hb_party_workspace_bytes_ex(size_t n, int k, int m, int dealer)
+{
+    if (!valid_slice(k, m) || n > HB_MAX_ELEMENTS || (dealer != HB_DEALER_PER_GATE && dealer != HB_DEALER_SHARED_MASK)) return 0;
+    return (size_t)party_layout(n, k, m, dealer).total_bytes;
+}
+
+size_t hb_party_wire_offset_ex(size_t n, int k, int m, int dealer, int party)
+{
+    if (!valid_slice(k, m) || n > HB_MAX_ELEMENTS || party < 0 || party > 1 ||
+        (dealer != HB_DEALER_PER_GATE && dealer != HB_DEALER_SHARED_MASK))
+        return 0;
+    return (size_t)party_layout(n, k, m, dealer).wire_off[party];
 }
 
 int hb_relu_party_static(const int64_t *share0, const int64_t *share1, size_t n, int k, int m, uint64_t seed,
@@ -674,7 +707,8 @@ int hb_relu_party_static(const int64_t *share0, const int64_t *share1, size_t n,
     void *ws = nullptr;
     const int st = party_scratch_of_current_device(&ws);
     if (st != HB_OK) return st;
-    return run_party(share0, share1, n, k, m, seed, out0, out1, ws, HB_PARTY_STATIC_BYTES, true, wire_bytes, stream);
+    return run_party(share0, share1, n, k, m, seed, HB_DEALER_PER_GATE, out0, out1, ws, HB_PARTY_STATIC_BYTES, true,
+                     wire_bytes, stream);
 }
 
 int hb_share_f32(const float *x, size_t n, uint64_t share_seed, int64_t *share0, int64_t *share1, void *stream)

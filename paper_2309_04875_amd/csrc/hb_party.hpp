@@ -17,6 +17,8 @@
 // Wire of party p (64-bit words): [2G gate 0][4G per round x R][ceil(n/64) B2A][2n multiply]; field j of a
 // group word sits at bit j*w and bits that belong to no element are zero.  The last round's P-update gate
 // is opened like every other gate (it is part of the opened-bit count) although nothing consumes its result.
+// On the shared-mask dealer layout the two gates of a round have one mask for P, so a round sends three words
+// per group (P ^ a once, then the two masked second operands): [3G per round x R].
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -28,7 +30,9 @@ namespace hb {
 
 struct PartyShape {
     int w, R, L, k;
-    uint64_t words_per_group;   // 5 (1 + 2R) + 1
+    int shared;                 // dealer layout: 0 one triple per gate, 1 one mask of P per round
+    int per_round;              // wire words a round sends per group: 4, or 3 on the shared-mask layout
+    uint64_t words_per_group;   // 5 (1 + 2R) + 1, or 5 + 8R + 1
     uint64_t field;             // 2^w - 1
     uint64_t ones;              // bit 0 of every field
     uint64_t live;              // all bits of the L fields
@@ -51,21 +55,30 @@ struct PartyTriple {
     uint64_t a, b, c;    // this party's shares of the gate's triple
 };
 
-// Party p's shares of the triple of gate q of group g.
+// Party p's shares of the triple of gate q of group g.  Standard layout: gate q owns words 5q .. 5q + 4
+// (a_0 a_1 b_0 b_1 c_0).  Shared-mask layout: gate 0 as before; round r owns words 5 + 8r .. 5 + 8r + 7 =
+// a_0 a_1 | b_0 b_1 c_0 of its G-update (gate 1 + 2r) | b_0 b_1 c_0 of its P-update (gate 2 + 2r).
 __device__ __forceinline__ PartyTriple party_triple(const PartyCtx &c, const PartyShape &s, int p, uint64_t g, int q, bool need_c)
 {
-    const uint64_t z = c.seedB + (g * s.words_per_group + 5 * (uint64_t)q + 1) * kGamma;
+    uint64_t wa = 5 * (uint64_t)q, wb = wa + 2;      // word of a_0, word of b_0 (a_1 and b_1, c_0 follow)
+    if (s.shared && q > 0) {
+        const int r = (q - 1) / 2;
+        wa = 5 + 8 * (uint64_t)r;
+        wb = wa + (((q - 1) & 1) ? 5 : 2);
+    }
+    const uint64_t za = c.seedB + (g * s.words_per_group + wa + 1) * kGamma;
+    const uint64_t zb = c.seedB + (g * s.words_per_group + wb + 1) * kGamma;
     PartyTriple t;
     if (p == 0) {
-        t.a = mix64(z);
-        t.b = mix64(z + 2 * kGamma);
-        t.c = need_c ? mix64(z + 4 * kGamma) : 0;
+        t.a = mix64(za);
+        t.b = mix64(zb);
+        t.c = need_c ? mix64(zb + 2 * kGamma) : 0;
     } else {
-        t.a = mix64(z + 1 * kGamma);
-        t.b = mix64(z + 3 * kGamma);
+        t.a = mix64(za + 1 * kGamma);
+        t.b = mix64(zb + 1 * kGamma);
         t.c = 0;
         if (need_c) {   // the dealer's c_1 = ((a_0 ^ a_1) & (b_0 ^ b_1)) ^ c_0
-            const uint64_t a0 = mix64(z), b0 = mix64(z + 2 * kGamma), c0 = mix64(z + 4 * kGamma);
+            const uint64_t a0 = mix64(za), b0 = mix64(zb), c0 = mix64(zb + 2 * kGamma);
             t.c = ((a0 ^ t.a) & (b0 ^ t.b)) ^ c0;
         }
     }
@@ -121,10 +134,15 @@ __global__ void __launch_bounds__(kPartyBlock) party_round_kernel(const PartyCtx
         const uint64_t d = c.wire[0][2 * g] ^ c.wire[1][2 * g], e = c.wire[0][2 * g + 1] ^ c.wire[1][2 * g + 1];
         G = party_and_finish(party_triple(c, s, p, g, 0, true), p, d, e);
     } else {
-        const uint64_t *w0 = c.wire[0] + 2 * c.groups + 4 * c.groups * (uint64_t)(r - 1) + 4 * g;
-        const uint64_t *w1 = c.wire[1] + 2 * c.groups + 4 * c.groups * (uint64_t)(r - 1) + 4 * g;
-        const uint64_t T = party_and_finish(party_triple(c, s, p, g, 1 + 2 * (r - 1), true), p, w0[0] ^ w1[0], w0[1] ^ w1[1]);
-        const uint64_t Pn = party_and_finish(party_triple(c, s, p, g, 2 + 2 * (r - 1), true), p, w0[2] ^ w1[2], w0[3] ^ w1[3]);
+        const uint64_t pr = (uint64_t)s.per_round;
+        const uint64_t *w0 = c.wire[0] + 2 * c.groups + pr * c.groups * (uint64_t)(r - 1) + pr * g;
+        const uint64_t *w1 = c.wire[1] + 2 * c.groups + pr * c.groups * (uint64_t)(r - 1) + pr * g;
+        // opened values of the previous round: d, e of its G-update, then d, e of its P-update (d is shared on
+        // the shared-mask layout)
+        const uint64_t dT = w0[0] ^ w1[0], eT = w0[1] ^ w1[1];
+        const uint64_t dP = s.shared ? dT : (w0[2] ^ w1[2]), eP = s.shared ? (w0[2] ^ w1[2]) : (w0[3] ^ w1[3]);
+        const uint64_t T = party_and_finish(party_triple(c, s, p, g, 1 + 2 * (r - 1), true), p, dT, eT);
+        const uint64_t Pn = party_and_finish(party_triple(c, s, p, g, 2 + 2 * (r - 1), true), p, dP, eP);
         G = c.G[p][g] ^ T;
         P = Pn;
     }
@@ -134,11 +152,15 @@ __global__ void __launch_bounds__(kPartyBlock) party_round_kernel(const PartyCtx
     const uint64_t keep = s.keep[r], live = party_live(c, s, g);
     const PartyTriple tT = party_triple(c, s, p, g, 1 + 2 * r, false);
     const PartyTriple tP = party_triple(c, s, p, g, 2 + 2 * r, false);
-    uint64_t *out = c.wire[p] + 2 * c.groups + 4 * c.groups * (uint64_t)r + 4 * g;
+    uint64_t *out = c.wire[p] + 2 * c.groups + (uint64_t)s.per_round * c.groups * (uint64_t)r + (uint64_t)s.per_round * g;
     out[0] = (P ^ tT.a) & live;
     out[1] = (((G << sh) & keep) ^ tT.b) & live;
-    out[2] = (P ^ tP.a) & live;
-    out[3] = (((P << sh) & keep) ^ tP.b) & live;
+    if (s.shared) {             // tP.a is the same word as tT.a: P ^ a has been sent already
+        out[2] = (((P << sh) & keep) ^ tP.b) & live;
+    } else {
+        out[2] = (P ^ tP.a) & live;
+        out[3] = (((P << sh) & keep) ^ tP.b) & live;
+    }
 }
 
 // ---- "sign": finish the last G-update, take the sign share of every field, mask it with the dealer bit --------
@@ -153,12 +175,13 @@ __global__ void __launch_bounds__(kPartyBlock) party_sign_kernel(const PartyCtx 
         G = party_and_finish(party_triple(c, s, p, g, 0, true), p, d, e);
     } else {
         const int r = s.R - 1;
-        const uint64_t *w0 = c.wire[0] + 2 * c.groups + 4 * c.groups * (uint64_t)r + 4 * g;
-        const uint64_t *w1 = c.wire[1] + 2 * c.groups + 4 * c.groups * (uint64_t)r + 4 * g;
+        const uint64_t pr = (uint64_t)s.per_round;
+        const uint64_t *w0 = c.wire[0] + 2 * c.groups + pr * c.groups * (uint64_t)r + pr * g;
+        const uint64_t *w1 = c.wire[1] + 2 * c.groups + pr * c.groups * (uint64_t)r + pr * g;
         G = c.G[p][g] ^ party_and_finish(party_triple(c, s, p, g, 1 + 2 * r, true), p, w0[0] ^ w1[0], w0[1] ^ w1[1]);
     }
     const uint64_t sum = c.S[p][g] ^ ((G << 1) & s.keep1);
-    const uint64_t wb = mix64(c.seedB + (g * s.words_per_group + 5 * (uint64_t)(1 + 2 * s.R) + 1) * kGamma);
+    const uint64_t wb = mix64(c.seedB + (g * s.words_per_group + s.words_per_group) * kGamma);   // the group's last word
     const uint64_t first = g * (uint64_t)s.L;
     const int cnt = (c.n - first >= (uint64_t)s.L) ? s.L : (int)(c.n - first);
     uint64_t zb = 0;
@@ -209,7 +232,7 @@ __global__ void __launch_bounds__(kPartyBlock) party_mul_send_kernel(const Party
         // the dealer's arithmetic share of its bit for party 1: r - r^A_0
         const uint64_t g = i / (uint64_t)s.L;
         const int j = (int)(i - g * (uint64_t)s.L);
-        const uint64_t wb = mix64(c.seedB + (g * s.words_per_group + 5 * (uint64_t)(1 + 2 * s.R) + 1) * kGamma);
+        const uint64_t wb = mix64(c.seedB + (g * s.words_per_group + s.words_per_group) * kGamma);
         const uint64_t r = ((wb >> (2 * j)) ^ (wb >> (2 * j + 1))) & 1;
         const uint64_t rA1 = r - rA0;
         const uint64_t beta = z ? (0 - rA1) : rA1;          // beta_1 = r^A_1 - 2 z r^A_1

@@ -16,7 +16,7 @@ HB_DEALER_PER_GATE, HB_DEALER_SHARED_MASK = 0, 1
 BASELINE_BITS_PER_ELEMENT = 29 * 64   # unpacked 64-bit ring, Sec. 2.3 accounting
 
 EXPORTS = ("hb_drelu", "hb_relu", "hb_sign_shares", "hb_open", "hb_relu_batch", "hb_drelu_batch", "hb_eco_scan", "hb_eco_choose",
-           "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_relu_party_static", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
+           "hb_share_f32", "hb_reveal_f32", "hb_sim_relu_f32", "hb_relu_party", "hb_relu_party_ex", "hb_party_workspace_bytes_ex", "hb_party_wire_words_ex", "hb_party_wire_offset_ex", "hb_relu_party_static", "hb_party_workspace_bytes", "hb_party_wire_words", "hb_party_wire_offset",
            "hb_drelu_ex", "hb_relu_ex", "hb_relu_batch_ex", "hb_drelu_batch_ex", "hb_plan_create", "hb_plan_run", "hb_plan_destroy",
            "hb_drelu_mp", "hb_relu_mp", "hb_opened_bits_mp",
            "hb_tensor_seed",
@@ -87,6 +87,14 @@ def load():
     lib.hb_sim_relu_f32.argtypes = [vp, sz, ci, ci, u64, u64, vp, vp]
     lib.hb_relu_party.restype = ci
     lib.hb_relu_party.argtypes = [vp, vp, sz, ci, ci, u64, vp, vp, vp, sz, u64p, vp]
+    lib.hb_relu_party_ex.restype = ci
+    lib.hb_relu_party_ex.argtypes = [vp, vp, sz, ci, ci, u64, ci, vp, vp, vp, sz, u64p, vp]
+    lib.hb_party_workspace_bytes_ex.restype = sz
+    lib.hb_party_workspace_bytes_ex.argtypes = [sz, ci, ci, ci]
+    lib.hb_party_wire_words_ex.restype = sz
+    lib.hb_party_wire_words_ex.argtypes = [sz, ci, ci, ci]
+    lib.hb_party_wire_offset_ex.restype = sz
+    lib.hb_party_wire_offset_ex.argtypes = [sz, ci, ci, ci, ci]
     lib.hb_relu_party_static.restype = ci
     lib.hb_relu_party_static.argtypes = [vp, vp, sz, ci, ci, u64, vp, vp, u64p, vp]
     lib.hb_party_workspace_bytes.restype = sz
@@ -364,9 +372,47 @@ def hb_party_wire_offset(n, k, m, party):
     return int(load().hb_party_wire_offset(int(n), int(k), int(m), int(party)))
 
 
+def hb_party_workspace_bytes_ex(n, k, m, dealer):
+    return int(load().hb_party_workspace_bytes_ex(int(n), int(k), int(m), int(dealer)))
+
+
+def hb_party_wire_words_ex(n, k, m, dealer):
+    return int(load().hb_party_wire_words_ex(int(n), int(k), int(m), int(dealer)))
+
+
+def hb_party_wire_offset_ex(n, k, m, dealer, party):
+    return int(load().hb_party_wire_offset_ex(int(n), int(k), int(m), int(dealer), int(party)))
+
+
+def hb_relu_party_ex(share0, share1, k, m, seed, dealer, out0=None, out1=None, workspace=None, stream=None):
+    """Party-faithful ReLU on a dealer layout; returns (out0, out1, wire0, wire1, wire_bytes) where wire_p is an
+    int64 view of party p's wire inside the workspace (a uint8 CUDA tensor, allocated here unless one is passed)."""
+    import torch
+    if out0 is None:
+        out0 = torch.empty_like(share0)
+    if out1 is None:
+        out1 = torch.empty_like(share1)
+    n = _tensor_args(share0, share1, out0, out1)
+    need = hb_party_workspace_bytes_ex(n, k, m, dealer)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=share0.device)
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous uint8 CUDA tensor")
+    wire_bytes = ctypes.c_uint64(0)
+    st = load().hb_relu_party_ex(share0.data_ptr(), share1.data_ptr(), n, int(k), int(m), int(seed) & (2**64 - 1),
+                                 int(dealer), out0.data_ptr(), out1.data_ptr(), workspace.data_ptr(),
+                                 workspace.numel(), ctypes.byref(wire_bytes), _stream_handle(stream))
+    _check(st)
+    words = hb_party_wire_words_ex(n, k, m, dealer)
+    wires = []
+    for p in (0, 1):
+        off = hb_party_wire_offset_ex(n, k, m, dealer, p)
+        wires.append(workspace[off:off + 8 * words].view(torch.int64))
+    return out0, out1, wires[0], wires[1], int(wire_bytes.value)
+
+
 def hb_relu_party(share0, share1, k, m, seed, out0=None, out1=None, workspace=None, stream=None):
-    """Party-faithful ReLU; returns (out0, out1, wire0, wire1, wire_bytes) where wire_p is an int64 view of
-    party p's wire inside the workspace (a uint8 CUDA tensor, allocated here unless one is passed)."""
+    """Party-faithful ReLU on the standard dealer layout (through the C entry point hb_relu_party)."""
     import torch
     if out0 is None:
         out0 = torch.empty_like(share0)
