@@ -98,23 +98,29 @@ def _time_launches(fn, torch, warm_ms=120.0, meas_ms=150.0, max_reps=4000):
     return e0.elapsed_time(e1) / reps
 
 
-def _clock_under(load_fn, torch, probes, dev, before=60, after=12, spins=40000):
-    """Shader clock (MHz) while `load_fn` launches run back to back: `before` launches are enqueued, then a
-    one-wavefront probe on a second stream (it takes a wave slot when one frees up and times a fixed dependent
-    chain against the 100 MHz counter), then `after` more launches, so the probe runs in the middle of a settled
-    load and never next to an idle GPU."""
+def _clock_under(load_fn, torch, probes, dev, launch_ms, spins=400000, reps=3):
+    """Shader clock (MHz) while `load_fn` launches run back to back.  A one-wavefront probe on a second stream takes
+    a wave slot when one frees up and times a fixed dependent chain of about 15 ms (many launches long: the clock
+    moves under the power limit, and windows of a millisecond read anything from 1.75 to 2.15 GHz) against the
+    100 MHz counter; launches of the load are enqueued before it (60 ms) and after it (40 ms), so it never runs next
+    to an idle GPU.  Median of `reps` probes."""
     side = torch.cuda.Stream()
-    stamps = torch.zeros(2, dtype=torch.int64, device=dev)
-    torch.cuda.synchronize()
-    for _ in range(before):
-        load_fn()
-    with torch.cuda.stream(side):
-        probes.clock_probe(spins, stamps)
-    for _ in range(after):
-        load_fn()
-    torch.cuda.synchronize()
-    ticks = stamps.cpu().tolist()
-    return 100.0 * ticks[0] / max(ticks[1], 1)
+    before = max(4, int(60.0 / launch_ms))
+    after = max(4, int(40.0 / launch_ms))
+    readings = []
+    for _ in range(reps):
+        stamps = torch.zeros(2, dtype=torch.int64, device=dev)
+        torch.cuda.synchronize()
+        for _ in range(before):
+            load_fn()
+        with torch.cuda.stream(side):
+            probes.clock_probe(spins, stamps)
+        for _ in range(after):
+            load_fn()
+        torch.cuda.synchronize()
+        ticks = stamps.cpu().tolist()
+        readings.append(100.0 * ticks[0] / max(ticks[1], 1))
+    return sorted(readings)[len(readings) // 2]
 
 
 def _issue_floor(consts, prefix, waves, launch_ms, clock_mhz):
@@ -190,19 +196,29 @@ def microbench(torch, hb, probes, workloads, dev):
     ms = _time_launches(lambda: hb.hb_open(x0, x1, False, out=o0), torch, 200.0, 200.0)
     say("%-22s %-44s %8.4f ms %8.1f GB/s" % ("hb_open", "24 B per element", ms, 24.0 * n / ms / 1e6))
     say()
-    say("# socket power (amd-smi metric -p, SOCKET_POWER) 1.2 s and 2.0 s into a steady load of about 3 s")
+    say("# socket power (amd-smi metric -p, SOCKET_POWER), two readings between 1.2 s and 2.5 s into a steady load of about 4 s")
     say("%-44s %8s %8s" % ("load", "W", "W"))
     torch.cuda.synchronize()
     time.sleep(3.0)
     say("%-44s %8s" % ("idle (3 s after the last kernel)", _socket_power()))
 
     def under(name, enqueue):
+        # the launches are enqueued from a second host thread (the launch queue is finite, so enqueueing seconds of
+        # work blocks its caller) while this thread reads the power
+        import threading
         torch.cuda.synchronize()
-        enqueue()
+        stream = torch.cuda.current_stream()
+
+        def feed():
+            with torch.cuda.stream(stream):
+                enqueue()
+        th = threading.Thread(target=feed)
+        th.start()
         time.sleep(1.2)
         p1 = _socket_power()
-        time.sleep(0.5)
+        time.sleep(0.4)
         p2 = _socket_power()
+        th.join()
         torch.cuda.synchronize()
         say("%-44s %8s %8s" % (name, p1, p2))
 
@@ -211,16 +227,16 @@ def microbench(torch, hb, probes, workloads, dev):
     q0, q1 = torch.empty_like(s0), torch.empty_like(s1)
     for idx in [names.index(t) for t in ("v_xor_b32", "v_bitop3_b32", "v_mul_lo_u32", "v_mad_u64_u32", "v_lshrrev_b64")]:
         r = probes.issue_probe(idx, 8, 2048)
-        launches = max(1, int(3000.0 / r["ms"]))
+        launches = max(1, int(4000.0 / r["ms"]))
         under(names[idx] + " on all compute units", lambda: probes.issue_load(idx, 8, 2048, launches))
     ms = _time_launches(lambda: hb.hb_relu(s0, s1, 12, 20, 7, q0, q1), torch)
-    under("hb_relu w = 8, 2^25 elements", lambda: [hb.hb_relu(s0, s1, 12, 20, 7, q0, q1) for _ in range(int(3000.0 / ms))])
+    under("hb_relu w = 8, 2^25 elements", lambda: [hb.hb_relu(s0, s1, 12, 20, 7, q0, q1) for _ in range(int(4000.0 / ms))])
     ms = _time_launches(lambda: hb.hb_drelu(s0, s1, 12, 20, 7, q0, q1), torch)
-    under("hb_drelu w = 8, 2^25 elements", lambda: [hb.hb_drelu(s0, s1, 12, 20, 7, q0, q1) for _ in range(int(3000.0 / ms))])
+    under("hb_drelu w = 8, 2^25 elements", lambda: [hb.hb_drelu(s0, s1, 12, 20, 7, q0, q1) for _ in range(int(4000.0 / ms))])
     ms = _time_launches(lambda: hb.hb_relu(s0, s1, 0, 64, 7, q0, q1), torch)
-    under("hb_relu w = 64, 2^25 elements", lambda: [hb.hb_relu(s0, s1, 0, 64, 7, q0, q1) for _ in range(int(3000.0 / ms))])
+    under("hb_relu w = 64, 2^25 elements", lambda: [hb.hb_relu(s0, s1, 0, 64, 7, q0, q1) for _ in range(int(4000.0 / ms))])
     ms = _time_launches(lambda: hb.hb_open(s0, s1, False, out=q0), torch)
-    under("hb_open, 2^25 elements", lambda: [hb.hb_open(s0, s1, False, out=q0) for _ in range(int(3000.0 / ms))])
+    under("hb_open, 2^25 elements", lambda: [hb.hb_open(s0, s1, False, out=q0) for _ in range(int(4000.0 / ms))])
 
 
 def main():
@@ -306,7 +322,7 @@ def main():
                 "algorithmic_bytes_per_launch": bytes_per_launch, "algorithmic_bytes_per_element": BYTES_PER_ELEMENT,
                 "target_frac": 0.60, "target_met": achieved_gbs / HBM_PEAK_GBS >= 0.60}
 
-    clock_mhz = None if args.no_extra else _clock_under(step, torch, probes, dev)
+    clock_mhz = None if args.no_extra else _clock_under(step, torch, probes, dev, avg_launch_ms)
     roofline_alu = _issue_floor(consts, "headline", waves_headline, avg_launch_ms, clock_mhz)
     if roofline_alu is not None:
         roofline_alu["kernel"] = kernel_name(8, "relu", True)
@@ -314,7 +330,8 @@ def main():
     spec0, s0, s1, o0, o1, seed0 = tensors[0]
     bits_w8 = opened / n_total
     bits_full_ring = hb.hb_opened_bits(True, 0, 64, 1)
-    extra = {"opened_bits_per_element": bits_w8,
+    extra = {"shader_clock_mhz_under_headline_kernel": clock_mhz,
+             "opened_bits_per_element": bits_w8,
              "opened_bits_ratio_vs_sec_2_3_unpacked_accounting": hb.BASELINE_BITS_PER_ELEMENT / bits_w8,
              "opened_bits_ratio_vs_this_library_at_0_64": bits_full_ring / bits_w8}
     configs = [{"name": "cfg3 resnet18 32x32 batch 512, (12,20) [headline, timed region]", "elements": n_total,
@@ -330,7 +347,7 @@ def main():
             hb.hb_relu(s0, s1, 0, 64, seed0, o0, o1)
         ms64 = _time_launches(relu64, torch, 200.0, 300.0)
         gbs64 = BYTES_PER_ELEMENT * spec0.n / (ms64 * 1e-3) / 1e9
-        clock64 = _clock_under(relu64, torch, probes, dev, before=30, after=8)
+        clock64 = _clock_under(relu64, torch, probes, dev, ms64)
         roofline_w64 = {"bound": "hbm", "achieved": gbs64, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": gbs64 / HBM_PEAK_GBS, "kernel": kernel_name(64), "elements": spec0.n,
                         "elements_per_s": spec0.n / (ms64 * 1e-3), "avg_launch_ms": ms64,
@@ -433,7 +450,7 @@ def main():
         def drelu8():
             hb.hb_drelu(s0, s1, k, m, seed0, o0, o1)
         ms = _time_launches(drelu8, torch)
-        extra["drelu_w8_shader_clock_mhz"] = _clock_under(drelu8, torch, probes, dev, before=200, after=40)
+        extra["drelu_w8_shader_clock_mhz"] = _clock_under(drelu8, torch, probes, dev, ms)
         extra["drelu_w8_elems_per_s"] = spec0.n / (ms * 1e-3)
         extra["drelu_w8_hbm_frac"] = BYTES_PER_ELEMENT * spec0.n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         ms = _time_launches(lambda: hb.hb_open(s0, s1, False, out=o0), torch)

@@ -499,7 +499,9 @@ struct SmallTraits {
     static constexpr int kPairs = (kTile / 2 + kWave - 1) / kWave;
     static constexpr int kWords = 10 * S::R + 1;                // evaluated dealer words of a group: 2R gates + B2A
     static constexpr int kWordsPerLane = (kWords + kSplit - 1) / kSplit;
-    static constexpr int kStride = kWords + (kWords % 2 ? 1 : 2);     // words of LDS per group (16-byte multiple)
+    // words of LDS per group: a multiple of 32 words plus 2, so that the 16 groups' 16-byte reads of one word
+    // fall into 16 different sets of four banks (and the stride stays a 16-byte multiple)
+    static constexpr int kStride = ((kWords + 31) / 32) * 32 + 2;
     static constexpr int kSliceBytes = T::kPacked ? 2 * kGroups * 8 : kTile * (int)sizeof(typename T::Entry);
 };
 
