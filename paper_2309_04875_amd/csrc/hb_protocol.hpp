@@ -95,17 +95,16 @@ __device__ __forceinline__ uint64_t bitop3(uint64_t a, uint64_t b, uint64_t c)
     return ((uint64_t)hi << 32) | lo;
 }
 
-// One Beaver AND on XOR-shared words, Z = U & V, returned as acc ^ Z share by share (acc = {0, 0} for the
-// plain gate; the G-update of a prefix round passes the old G).  zq is the generator state of the gate's first
-// dealer word; the five words a_0 a_1 b_0 b_1 c_0 are consecutive outputs.  U is masked by a, V by b.
-// The gate sees U and V only through the two openings, and an opening is the XOR of what the two parties
-// send, (U_0 ^ a_0) ^ (U_1 ^ a_1) = (U_0 ^ U_1) ^ (a_0 ^ a_1); the caller passes Ux = U_0 ^ U_1 and
-// Vx = (V_0 ^ V_1) before the field mask `keep` that confines a shifted operand to its field (all ones when
-// the operand is not shifted).  Party 0 takes the public d & e term.
 struct GateWords {   // the five dealer words of one AND gate, in stream order
     uint64_t a0, a1, b0, b1, c0;
 };
 
+// One Beaver AND on XOR-shared words, Z = U & V, returned as acc ^ Z share by share (acc = {0, 0} for the
+// plain gate; the G-update of a prefix round passes the old G).  U is masked by a, V by b.
+// The gate sees U and V only through the two openings, and an opening is the XOR of what the two parties
+// send, (U_0 ^ a_0) ^ (U_1 ^ a_1) = (U_0 ^ U_1) ^ (a_0 ^ a_1); the caller passes Ux = U_0 ^ U_1 and
+// Vx = (V_0 ^ V_1) before the field mask `keep` that confines a shifted operand to its field (all ones when
+// the operand is not shifted).  Party 0 takes the public d & e term.
 __device__ __forceinline__ Pair beaver_and_words(const GateWords &t, uint64_t Ux, uint64_t Vx, uint64_t keep, Pair acc)
 {
     const uint64_t a0 = t.a0, a1 = t.a1, b0 = t.b0, b1 = t.b1, c0 = t.c0;
@@ -121,6 +120,8 @@ __device__ __forceinline__ Pair beaver_and_words(const GateWords &t, uint64_t Ux
     return Z;
 }
 
+// The same gate drawing its words inline: zq is the generator state of the gate's first dealer word; the five
+// words a_0 a_1 b_0 b_1 c_0 are consecutive outputs.
 __device__ __forceinline__ Pair beaver_and(uint64_t zq, uint64_t Ux, uint64_t Vx, uint64_t keep, Pair acc)
 {
     GateWords t;
