@@ -320,7 +320,10 @@ def main():
                                 "counter reads for a streaming kernel of known size; profiles/)",
                 "kernel": kernel_name(8, "relu", True), "avg_launch_ms": avg_launch_ms,
                 "algorithmic_bytes_per_launch": bytes_per_launch, "algorithmic_bytes_per_element": BYTES_PER_ELEMENT,
-                "target_frac": 0.60, "target_met": achieved_gbs / HBM_PEAK_GBS >= 0.60}
+                "target_frac": 0.60, "target_met": achieved_gbs / HBM_PEAK_GBS >= 0.60,
+                "valu_busy_pct_profiled": consts.get("headline.valu_busy_pct"),
+                "mean_occupancy_per_cu_profiled": consts.get("headline.mean_occupancy_per_cu"),
+                "vgprs": consts.get("headline.vgprs")}
 
     clock_mhz = None if args.no_extra else _clock_under(step, torch, probes, dev, avg_launch_ms)
     roofline_alu = _issue_floor(consts, "headline", waves_headline, avg_launch_ms, clock_mhz)
@@ -354,6 +357,8 @@ def main():
                         "opened_bits_per_element": bits_full_ring,
                         "valu_insts_per_element": consts.get("w64.valu_insts_per_wave"),
                         "valu_busy_pct_profiled": consts.get("w64.valu_busy_pct"),
+                        "mean_occupancy_per_cu_profiled": consts.get("w64.mean_occupancy_per_cu"),
+                        "vgprs": consts.get("w64.vgprs"),
                         "binding": _issue_floor(consts, "w64", (spec0.n + 63) // 64, ms64, clock64)}
 
         # ---- the other named workloads ---------------------------------------------------------------------
@@ -457,6 +462,8 @@ def main():
         extra["open_copy_ceiling_gbs"] = 24 * spec0.n / (ms * 1e-3) / 1e9
         ms = _time_launches(lambda: probes.stream_copy(s0, s1, o0, o1, True, False), torch)
         extra["stream_2in_2out_ceiling_gbs"] = 32 * spec0.n / (ms * 1e-3) / 1e9
+        roofline["frac_of_2in_2out_copy_ceiling"] = achieved_gbs / extra["stream_2in_2out_ceiling_gbs"]
+        roofline_w64["frac_of_2in_2out_copy_ceiling"] = gbs64 / extra["stream_2in_2out_ceiling_gbs"]
         ws = torch.empty(hb.hb_party_workspace_bytes(spec0.n, k, m), dtype=torch.uint8, device=dev)
         ms = _time_launches(lambda: hb.hb_relu_party(s0, s1, k, m, seed0, o0, o1, ws), torch)
         extra["relu_party_w8_elems_per_s"] = spec0.n / (ms * 1e-3)
