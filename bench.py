@@ -220,15 +220,24 @@ def microbench(torch, hb, probes, workloads, dev):
         p2 = _socket_power()
         th.join()
         torch.cuda.synchronize()
-        say("%-44s %8s %8s" % (name, p1, p2))
+        say("%-44s %8s %8s" % (name[:44], p1, p2))
+        return p2
 
     spec = workloads.resnet18_cifar_batch512()[0]
     _, s0, s1 = workloads.materialize_on_device(spec, dev)
     q0, q1 = torch.empty_like(s0), torch.empty_like(s1)
-    for idx in [names.index(t) for t in ("v_xor_b32", "v_bitop3_b32", "v_mul_lo_u32", "v_mad_u64_u32", "v_lshrrev_b64")]:
-        r = probes.issue_probe(idx, 8, 2048)
+    idle = _socket_power()
+    for idx in [names.index(t) for t in ("v_xor_b32", "v_bitop3_b32", "v_mul_lo_u32", "v_mad_u64_u32", "v_lshrrev_b64",
+                                         "16-wave groups: xor x128 / mul_lo x128, free-running",
+                                         "16-wave groups: xor x128 / mul_lo x128, barrier after each run")]:
+        iters = 256 if names[idx].startswith("16-wave") else 2048
+        r = probes.issue_probe(idx, 8, iters)
         launches = max(1, int(4000.0 / r["ms"]))
-        under(names[idx] + " on all compute units", lambda: probes.issue_load(idx, 8, 2048, launches))
+        p = under(names[idx] + " on all compute units", lambda: probes.issue_load(idx, 8, iters, launches))
+        if p and idle:
+            rate = r["instructions_per_wave"] * 8 * SIMDS / (r["ms"] * 1e-3)       # wavefront-instructions per second
+            say("%-44s %8.2f nJ per wavefront-instruction above idle (%.2f cycles each at %.0f MHz)"
+                % ("", (p - idle) / rate * 1e9, r["cycles_per_instruction"], r["mhz"]))
     ms = _time_launches(lambda: hb.hb_relu(s0, s1, 12, 20, 7, q0, q1), torch)
     under("hb_relu w = 8, 2^25 elements", lambda: [hb.hb_relu(s0, s1, 12, 20, 7, q0, q1) for _ in range(int(4000.0 / ms))])
     ms = _time_launches(lambda: hb.hb_drelu(s0, s1, 12, 20, 7, q0, q1), torch)
