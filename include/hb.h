@@ -108,23 +108,6 @@ HB_API int hb_relu_batch(const hb_tensor *tensors, size_t count, uint64_t *opene
 HB_API int hb_drelu_batch(const hb_tensor *tensors, size_t count, uint64_t *opened_bits, void *stream);
 
 /*
- * A set of tensors prepared once and issued many times (the (k, m) of every ReLU layer are fixed offline, Sec. 4.2,
- * and an inference engine runs the same layers on the same buffers step after step).  hb_plan_create checks the
- * descriptors exactly as hb_relu_batch_ex / hb_drelu_batch_ex do (relu != 0: ReLU, else DReLU; `dealer`: the
- * layout) and records the launches; hb_plan_run only enqueues them on `stream` -- the same kernels, the same
- * result shares -- at a fraction of the host cost per call.  The plan holds device addresses, not memory: the
- * caller keeps the buffers alive and at the same place while the plan is used (contents may change between runs),
- * and the device that was current at creation must be current at every run.  `tensors` is a HOST array read
- * before hb_plan_create returns; *plan receives the handle (host memory owned by the library, released by
- * hb_plan_destroy; NULL on error).  opened_bits (HOST, may be NULL) receives the set's total at every run.
- * A plan may be run from several host threads and on any stream; it is never modified after creation.
- */
-typedef struct hb_plan hb_plan;
-HB_API int hb_plan_create(const hb_tensor *tensors, size_t count, int relu, int dealer, hb_plan **plan);
-HB_API int hb_plan_run(const hb_plan *plan, uint64_t *opened_bits, void *stream);
-HB_API void hb_plan_destroy(hb_plan *plan);
-
-/*
  * Dealer layouts.  In a prefix round of the adder (Sec. 2.2, Sec. 4.2) both AND gates have the old propagate
  * word P as their first operand.  HB_DEALER_PER_GATE gives every gate its own Beaver triple (the plain reading:
  * 4w opened bits per round).  HB_DEALER_SHARED_MASK lets the two gates of a round share the mask a of P, with
@@ -145,6 +128,23 @@ HB_API int hb_relu_ex(const int64_t *share0, const int64_t *share1, size_t n, in
                       int64_t *out0, int64_t *out1, uint64_t *opened_bits, void *stream);
 HB_API int hb_relu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64_t *opened_bits, void *stream);
 HB_API int hb_drelu_batch_ex(const hb_tensor *tensors, size_t count, int dealer, uint64_t *opened_bits, void *stream);
+
+/*
+ * A set of tensors prepared once and issued many times (the (k, m) of every ReLU layer are fixed offline, Sec. 4.2,
+ * and an inference engine runs the same layers on the same buffers step after step).  hb_plan_create checks the
+ * descriptors exactly as hb_relu_batch_ex / hb_drelu_batch_ex do (relu != 0: ReLU, else DReLU; `dealer`: the
+ * layout) and records the launches; hb_plan_run only enqueues them on `stream` -- the same kernels, the same
+ * result shares -- at a fraction of the host cost per call.  The plan holds device addresses, not memory: the
+ * caller keeps the buffers alive and at the same place while the plan is used (contents may change between runs),
+ * and the device that was current at creation must be current at every run.  `tensors` is a HOST array read
+ * before hb_plan_create returns; *plan receives the handle (host memory owned by the library, released by
+ * hb_plan_destroy; NULL on error).  opened_bits (HOST, may be NULL) receives the set's total at every run.
+ * A plan may be run from several host threads and on any stream; it is never modified after creation.
+ */
+typedef struct hb_plan hb_plan;
+HB_API int hb_plan_create(const hb_tensor *tensors, size_t count, int relu, int dealer, hb_plan **plan);
+HB_API int hb_plan_run(const hb_plan *plan, uint64_t *opened_bits, void *stream);
+HB_API void hb_plan_destroy(hb_plan *plan);
 
 /*
  * More than two parties (Sec. 2.2 "Operation of CrypTen": a secret is split into p >= 2 arithmetic shares;
